@@ -1,0 +1,172 @@
+"""Benchmark of the fused linear-cross-entropy hot path on one MI355X.
+
+One "step" = cce_forward_ex + cce_backward_ex (dense backward: gradient filter off, so
+no work is skipped) on the Gemma-2-2B-shaped synthetic workload (N=8192, D=2304,
+|V|=256000, bf16, soft-cap 30), inputs resident in HBM.  Prints ONE JSON line with the
+whole-job throughput, a roofline object for the forward matmul-LSE kernel (bf16 MFMA
+bound) and the fp64 CPU oracle timed on a bounded sample of the same workload.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16, vendor figure (no sparsity)
+
+
+def cpu_baseline(w, rows):
+    """The oracle as it stands, forward + backward, on the first `rows` tokens."""
+    from oracle import cce_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    E, C = w.E64(np.arange(rows)), w.C64()
+    t = w.targets[:rows]
+    lam = np.full(rows, 1.0 / rows)
+    t0 = time.perf_counter()
+    loss, lse = O.forward(E, C, t, w.softcap, w.ignore_index)
+    O.backward(E, C, t, lse, lam, w.softcap, w.ignore_index)
+    dt = time.perf_counter() - t0
+    return {"value": rows / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": "first %d of %d tokens, full D and |V|, fp64 numpy forward+backward, %.1f s"
+                      % (rows, w.N, dt),
+            "host_cores_visible": len(os.sched_getaffinity(0))}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="gemma2_2b")
+    ap.add_argument("--cpu-rows", type=int, default=192)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (sharding is described in DESIGN.md); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2411_09009_amd as L
+    from workloads import make
+
+    L.load()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    w = make(args.workload)
+    E = torch.from_numpy(w.E.view(np.int16)).to(dev).view(torch.bfloat16)
+    C = torch.from_numpy(w.C.view(np.int16)).to(dev).view(torch.bfloat16)
+    tg = torch.from_numpy(w.targets).to(dev)
+    dloss = torch.from_numpy(w.mean_dloss()).to(dev)
+    N, D, V = w.N, w.D, w.V
+
+    def opts(eps, ws):
+        return L.make_opts(L.CCE_BF16, filter_eps=eps, workspace=ws)
+
+    o0 = L.make_opts(L.CCE_BF16)
+    fwd_bytes = L.cce_workspace_bytes(L.CCE_OP_FORWARD, N, D, V, o0)
+    bwd_bytes = L.cce_workspace_bytes(L.CCE_OP_BACKWARD, N, D, V, o0)
+    ws_f = torch.empty(fwd_bytes, dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(bwd_bytes, dtype=torch.uint8, device=dev)
+    loss = torch.empty(N, dtype=torch.float32, device=dev)
+    lse = torch.empty(N, dtype=torch.float32, device=dev)
+    dE = torch.empty_like(E)
+    dC = torch.empty_like(C)
+    of, ob_dense, ob_filt = opts(None, ws_f), opts(0.0, ws_b), opts(None, ws_b)
+
+    def fwd():
+        L.cce_forward_ex(E, C, tg, w.softcap, w.ignore_index, of, out_loss=loss, out_lse=lse)
+
+    def bwd(o):
+        L.cce_backward_ex(E, C, tg, lse, dloss, w.softcap, w.ignore_index, o, out_dE=dE, out_dC=dC)
+
+    for _ in range(args.warmup):
+        fwd()
+        bwd(ob_dense)
+    torch.cuda.synchronize()
+
+    # timed region: K steps, HIP events on the stream the kernels are launched on
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        ev[k][0].record()
+        fwd()
+        ev[k][1].record()
+        bwd(ob_dense)
+        ev[k][2].record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    fwd_ms = float(np.mean([ev[k][0].elapsed_time(ev[k][1]) for k in range(args.steps)]))
+    bwd_ms = float(np.mean([ev[k][1].elapsed_time(ev[k][2]) for k in range(args.steps)]))
+    ms_per_step = wall_ms / args.steps
+
+    # filtered backward (the library default), reported beside the dense one
+    for _ in range(2):
+        bwd(ob_filt)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        bwd(ob_filt)
+    e1.record()
+    torch.cuda.synchronize()
+    bwd_filt_ms = e0.elapsed_time(e1) / args.steps
+    total, kept = L.cce_backward_filter_stats(ws_b)
+    dE_f, dC_f = dE.float().clone(), dC.float()
+    bwd(ob_dense)
+    torch.cuda.synchronize()
+    err_dE = float((dE_f - dE.float()).norm() / dE.float().norm())
+    err_dC = float((dC_f - dC.float()).norm() / dC.float().norm())
+    del dE_f, dC_f
+
+    fwd_flop = 2.0 * N * D * V
+    fwd_tflops = fwd_flop / (fwd_ms * 1e-3) / 1e12
+    bwd_tflops = 3.0 * fwd_flop / (bwd_ms * 1e-3) / 1e12
+    out = {
+        "metric": "fused linear-CE fwd+bwd tokens/sec at Gemma-2-2B shape; % bf16 MFMA peak",
+        "value": N / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "%s N=%d D=%d V=%d softcap=%g" % (w.spec.name, N, D, V, w.softcap),
+                   "backward": "dense (gradient filter off)"},
+        "fwd_ms": fwd_ms,
+        "bwd_dense_ms": bwd_ms,
+        "fwd_tokens_per_s": N / (fwd_ms * 1e-3),
+        "bwd_dense_tflops": bwd_tflops,
+        "frac_mfma_peak_fwd_bwd": (4.0 * fwd_flop / (ms_per_step * 1e-3) / 1e12) / MFMA_BF16_PEAK_TFLOPS,
+        "bwd_filtered": {"ms": bwd_filt_ms, "blocks_kept": kept, "blocks_total": total,
+                         "dE_rel_fro_vs_dense": err_dE, "dC_rel_fro_vs_dense": err_dC},
+        "extra_hbm_bytes": {"forward_workspace": fwd_bytes, "backward_workspace": bwd_bytes,
+                            "logits_avoided_fp32": 4 * N * V},
+        "roofline": {"kernel": "fwd_lse_mfma_kernel (timed as cce_forward_ex: + finalize, <1%)",
+                     "bound": "mfma", "achieved": fwd_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": fwd_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, min(args.cpu_rows, N))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

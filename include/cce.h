@@ -1,0 +1,163 @@
+/*
+ * cce.h - C ABI of the MI355X (gfx950) fused linear cross-entropy library.
+ *
+ * The library computes the per-token cross-entropy of a linear classifier
+ * without ever writing the N x |V| logit matrix to device memory
+ * (paper Section 3, Eq. 4:  l_i = C_{x_i}^T E_i - log sum_j exp(C_j^T E_i);
+ * this library returns the negative of l_i, the usual NLL).
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers on the current HIP device.  The
+ *     caller owns every buffer; the library only reads inputs and writes the
+ *     outputs / the workspace named in the call.
+ *   - E is [N, D] and C is [V, D], row-major, contiguous (leading dimension D):
+ *     the paper's D x N / D x |V| matrices "indexed by column" (Appendix A).
+ *     Element type: bfloat16 (CCE_BF16) or float (CCE_F32); E, C, out_dE and
+ *     out_dC share it.  Pointers must be 16-byte aligned.
+ *   - targets is int64 [N].  A token is "ignored" when its target equals
+ *     ignore_index or lies outside [0, V): it gets loss 0, contributes nothing
+ *     to dE / dC, and its dLoss entry is not read (Appendix B: ignored tokens
+ *     change neither loss nor gradient).
+ *   - softcap == 0 disables logit soft-capping; softcap > 0 replaces every
+ *     logit z by softcap * tanh(z / softcap) (the soft-capping named in
+ *     Table A2; formula is this library's reading).  Negative or NaN: CCE_EINVAL.
+ *   - Calls are asynchronous on a HIP stream (opts->stream, or the null stream
+ *     for the plain entry points) and never synchronise it.  Work that the
+ *     library spreads over helper streams is joined back into that stream
+ *     before the call returns.
+ *   - Return value: CCE_OK (0) or a negative cce_status.  On CCE_EINVAL,
+ *     CCE_EUNSUPPORTED and CCE_EWORKSPACE nothing has been launched and no
+ *     output has been written.
+ *   - Results are bitwise reproducible from call to call: no atomics and no
+ *     lock-ordered reductions are used (the paper's Alg. 2 / Alg. 4 use
+ *     spin-locks; Section 4.2 itself notes alternatives may be preferable).
+ */
+#ifndef CCE_H_
+#define CCE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum cce_status {
+  CCE_OK = 0,
+  CCE_EINVAL = -1,       /* null / misaligned pointer, non-positive size, bad softcap or eps */
+  CCE_EWORKSPACE = -2,   /* opts->workspace missing or smaller than the minimum */
+  CCE_EUNSUPPORTED = -3, /* unknown dtype or flag */
+  CCE_EHIP = -4          /* a HIP runtime call failed; see cce_strerror */
+} cce_status;
+
+enum { CCE_BF16 = 0, CCE_F32 = 1 };
+
+/* cce_opts.flags */
+enum {
+  CCE_FILTER_DE = 1u << 0,   /* apply gradient filtering to dE (Section 4.3) */
+  CCE_FILTER_DC = 1u << 1,   /* apply gradient filtering to dC; clearing only this bit is the
+                                paper's "CCE-Kahan-FullC" choice, clearing only FILTER_DE "FullE" */
+  CCE_VOCAB_SORT = 1u << 2,  /* forward: also accumulate the mean logit of every vocabulary entry;
+                                backward: walk the vocabulary in order of that mean (Section 4.3,
+                                "Vocabulary sorting").  Needs the same workspace in both calls. */
+  CCE_PLAIN_KERNELS = 1u << 3 /* run the plain fp32-FMA kernels instead of the MFMA ones (always used
+                                for CCE_F32 and for shapes the MFMA kernels do not take) */
+};
+
+/* cce_workspace_bytes(op, ...) */
+enum {
+  CCE_OP_FORWARD = 0,        /* exact requirement of cce_forward_ex */
+  CCE_OP_BACKWARD = 1,       /* recommended size for cce_backward_ex (fastest slab width) */
+  CCE_OP_BACKWARD_MIN = 2    /* smallest size cce_backward_ex accepts (narrowest slab) */
+};
+
+typedef struct cce_opts {
+  int dtype;              /* CCE_BF16 or CCE_F32 */
+  uint32_t flags;         /* CCE_FILTER_* | CCE_VOCAB_SORT | CCE_PLAIN_KERNELS */
+  float filter_eps;       /* gradient-filter threshold on |softmax - onehot|; 0 disables filtering.
+                             The paper's value for bf16 is 2^-12 (Section 4.3). */
+  void* workspace;        /* device scratch, 256-byte aligned, owned by the caller */
+  size_t workspace_bytes;
+  void* stream;           /* hipStream_t; NULL = null stream */
+} cce_opts;
+
+/* Fills *opts with the defaults the plain entry points use for `dtype`:
+ * bf16: FILTER_DE | FILTER_DC, filter_eps = 2^-12;  f32: no filtering (eps = 0).
+ * workspace = NULL, stream = NULL. */
+void cce_default_opts(int dtype, cce_opts* opts);
+
+/*
+ * Forward (Alg. 1 indexed matmul + Alg. 2 linear-log-sum-exp, Eq. 4).
+ *   out_lse [N] float:  log sum_j exp(a_ij) for EVERY row, ignored or not.
+ *   out_loss[N] float:  out_lse_i - a_{i,x_i} for valid tokens, 0 for ignored ones.
+ * Extra device memory: the workspace only, O(N) floats (plus O(V) with
+ * CCE_VOCAB_SORT); the logits live in registers / LDS.
+ *
+ * cce_forward: bf16 inputs, null stream, library-owned workspace (allocated
+ * with hipMalloc on first use per device, grown when a larger problem arrives,
+ * kept until the process ends; calls on one device must not overlap).
+ */
+int cce_forward(const void* E, const void* C, const int64_t* targets,
+                int64_t N, int64_t D, int64_t V,
+                float softcap, int64_t ignore_index,
+                float* out_loss, float* out_lse);
+
+int cce_forward_ex(const void* E, const void* C, const int64_t* targets,
+                   int64_t N, int64_t D, int64_t V,
+                   float softcap, int64_t ignore_index,
+                   float* out_loss, float* out_lse, const cce_opts* opts);
+
+/*
+ * Backward (Alg. 4, the merged linear-cross-entropy backward; gradient formula
+ * of Section 4.3):  with S = exp(a - lse), G = S - onehot(x) (0 for ignored rows),
+ *   out_dE[N, D] = sum_j dLoss_i G_ij a'_ij C_j,   out_dC[V, D] = sum_i dLoss_i G_ij a'_ij E_i,
+ * a'_ij = 1 - (a_ij / softcap)^2 with soft-capping, else 1.
+ *   lse   [N] float: out_lse of the forward call on the same inputs.
+ *   dLoss [N] float: upstream gradient of out_loss.
+ * Both outputs are OVERWRITTEN (not accumulated into), in the dtype of E / C,
+ * accumulated in fp32 and rounded once.
+ * Gradient filtering (Section 4.3): a block of G whose entries are all below
+ * filter_eps in magnitude is left out of the products that have their
+ * CCE_FILTER_* bit set.  Block shape is an implementation choice
+ * (cce_filter_block reports it).
+ * Extra device memory: the workspace, independent of |V|: a slab of the
+ * gradient-of-logits matrix plus an fp32 [N, D] accumulator.
+ *
+ * cce_backward: bf16, null stream, filtering on at 2^-12, library-owned workspace.
+ */
+int cce_backward(const void* E, const void* C, const int64_t* targets,
+                 int64_t N, int64_t D, int64_t V,
+                 float softcap, int64_t ignore_index,
+                 const float* lse, const float* dLoss,
+                 void* out_dE, void* out_dC);
+
+int cce_backward_ex(const void* E, const void* C, const int64_t* targets,
+                    int64_t N, int64_t D, int64_t V,
+                    float softcap, int64_t ignore_index,
+                    const float* lse, const float* dLoss,
+                    void* out_dE, void* out_dC, const cce_opts* opts);
+
+/* Workspace size in bytes for `op` (CCE_OP_*) at this shape and these options
+ * (dtype and flags are read; workspace fields are not).  0 on invalid arguments. */
+size_t cce_workspace_bytes(int op, int64_t N, int64_t D, int64_t V, const cce_opts* opts);
+
+/* Rows (tokens) x columns (vocabulary entries) of the block the gradient filter
+ * tests as a unit, for the kernels `opts` selects at this shape. */
+void cce_filter_block(int64_t N, int64_t D, int64_t V, const cce_opts* opts,
+                      int* block_rows, int* block_cols);
+
+/* Host-side counters of the last cce_backward(_ex) call that used this
+ * workspace: number of filter blocks visited and number kept.  Synchronises
+ * `stream` (this is a reporting call, not part of the hot path).
+ * Returns CCE_OK or a negative status. */
+int cce_backward_filter_stats(const void* workspace, void* stream,
+                              uint64_t* blocks_total, uint64_t* blocks_kept);
+
+/* Static, NUL-terminated description of a status code; for CCE_EHIP the text of
+ * the last failing HIP call on this thread. */
+const char* cce_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CCE_H_ */

@@ -1,0 +1,349 @@
+// Backward pass on MFMA (paper Alg. 4, merged linear-cross-entropy backward), gfx950.
+//
+// The algorithm of the paper walks all (token block, vocabulary block) pairs,
+// recomputes the logit block, forms G = softmax - onehot, and immediately adds
+// the block's contribution to dE and dC in global memory under locks.  On this
+// chip a dense sweep of that form is bound by the read-modify-write traffic of
+// the two fp32 output tiles, so the pass is restructured around vocabulary
+// slabs; within a slab
+//   1. recompute kernel: logit tiles as in the forward pass, then
+//      gz = dloss * (exp(a - lse) - onehot) * a'  written once as bf16, both
+//      token-major (GZ) and vocabulary-major (GZT), plus block flags for the
+//      gradient filter;
+//   2. dC[slab] = GZT * E^T-slice product, final after one pass over the tokens;
+//   3. dE += GZ * C^T-slab product, accumulated in fp32 across slabs by plain
+//      (exclusive-owner) read-modify-write.
+// All three are the same NT MFMA contraction (mfma_tile.h); the operands that
+// are not K-contiguous in the caller's layout (E and the C slab, contracted over
+// tokens / vocabulary) are transposed once into the workspace.
+#include "kernels.h"
+#include "mfma_tile.h"
+
+namespace cce {
+
+namespace {
+
+// ------------------------------------------------------------------ transpose
+// out[c][r] = r < rows_valid ? in[r][c] : 0     (out is [cols][rows_padded])
+__global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t* __restrict__ in, int rows_valid,
+                                                             int rows_padded, int cols, int64_t ld_in,
+                                                             uint16_t* __restrict__ out) {
+  __shared__ uint16_t tile[64][66];
+  const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int j = ty; j < 64; j += 4) {
+    int r = r0 + j, c = c0 + tx;
+    tile[j][tx] = (r < rows_valid && c < cols) ? in[(int64_t)r * ld_in + c] : (uint16_t)0;
+  }
+  __syncthreads();
+  for (int j = ty; j < 64; j += 4) {
+    int c = c0 + j, r = r0 + tx;
+    if (c < cols && r < rows_padded) out[(int64_t)c * rows_padded + r] = tile[tx][j];
+  }
+}
+
+enum { kNoCap = 0, kCap = 1 };
+constexpr int kMaxKSteps = 2048;   // longest filtered contraction: 131072 / 64
+
+// ------------------------------------------------------------------ recompute + G
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void bwd_recompute_mfma_kernel(BwdCommon c, BwdMfmaSlab sl, int splits,
+                                                                      int tiles_per_split) {
+  __shared__ __attribute__((aligned(1024))) char lds[kLdsBytes];
+  TileCoords tc;
+  tc.init();
+  const int n_tile = blockIdx.x / splits, split = blockIdx.x % splits;
+  const int v_tiles = sl.vs / kTileR;
+  const int t0 = split * tiles_per_split, t1 = min(t0 + tiles_per_split, v_tiles);
+  const int n0 = n_tile * kTileC;
+  const int64_t ld_bytes = (int64_t)c.D * 2;
+  const int KT = c.D / kTileK;
+
+  uint32_t offQ[4];
+  dma_offsets(tc, min(kTileC, c.N - n0), ld_bytes, offQ);
+  const char* gQ = (const char*)c.E + (int64_t)n0 * ld_bytes;
+
+  // per-lane token data for the lane's two token columns
+  float lse2[kCB], lam[kCB];
+  int tgt[kCB], ncol[kCB];
+#pragma unroll
+  for (int cb = 0; cb < kCB; ++cb) {
+    const int n = n0 + tc.wave_c * kWaveCols + cb * 32 + (tc.lane & 31);
+    ncol[cb] = n;
+    lse2[cb] = 0.f;
+    lam[cb] = 0.f;
+    tgt[cb] = -1;
+    if (n < c.N) {
+      const int64_t t = c.targets[n];
+      if (t != c.ignore_index && t >= 0 && t < c.V) {
+        tgt[cb] = (int)t;
+        lam[cb] = c.dloss[n];
+        lse2[cb] = c.lse[n] * kLog2e;
+      }
+    }
+  }
+
+  f32x16 acc[kRB][kCB];
+#pragma unroll
+  for (int rb = 0; rb < kRB; ++rb)
+#pragma unroll
+    for (int cb = 0; cb < kCB; ++cb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[rb][cb][i] = 0.f;
+
+  const float cap_scale = MODE == kCap ? 2.f * kLog2e / c.softcap : 0.f;
+  const float cap_l2 = MODE == kCap ? c.softcap * kLog2e : kLog2e;
+  const float eps = c.eps;
+  const char* P = (const char*)c.C + (int64_t)sl.v0 * ld_bytes;
+
+  sweep_tiles(tc, lds, P, c.V - sl.v0, ld_bytes, t0, t1, gQ, offQ, KT, acc, [&](int t) {
+    const int vl_base = t * kTileR + tc.wave_r * kWaveRows;   // slab-local vocabulary row of this wave
+    bool sig[2] = {false, false};                              // halves rb {0,1} and {2,3}
+#pragma unroll
+    for (int cb = 0; cb < kCB; ++cb) {
+      const bool tok = tgt[cb] >= 0;
+      // Keep the store-address arithmetic inside the epilogue: derived from an opaque copy of
+      // the column index, it cannot be hoisted out of the tile loop and held in registers
+      // across the MFMA stages.  Offsets are 32-bit element indices (the dispatcher keeps
+      // Np * vs below 2^30).
+      uint32_t nc = (uint32_t)ncol[cb];
+      asm volatile("" : "+v"(nc));
+      const uint32_t gz_row = nc * (uint32_t)sl.vs;
+#pragma unroll
+      for (int rb = 0; rb < kRB; ++rb) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          bf16 o[4];
+          const int vl = vl_base + rb * 32 + 8 * g + 4 * (tc.lane >> 5);
+          uint32_t gzt_off = (uint32_t)vl * (uint32_t)sl.Np + nc;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const float z = acc[rb][cb][g * 4 + j];
+            acc[rb][cb][g * 4 + j] = 0.f;
+            float a2, dcap;
+            if (MODE == kCap) {
+              float e = __builtin_amdgcn_exp2f(z * cap_scale);
+              float r = __builtin_amdgcn_rcpf(1.f + e);
+              float th = fmaf(-2.f, r, 1.f);           // tanh(z / cap)
+              a2 = cap_l2 * th;
+              dcap = fmaf(-th, th, 1.f);
+            } else {
+              a2 = z * kLog2e;
+              dcap = 1.f;
+            }
+            const int v = sl.v0 + vl + j;
+            float gval = __builtin_amdgcn_exp2f(a2 - lse2[cb]) - (v == tgt[cb] ? 1.f : 0.f);
+            const bool live = tok && v < c.V;
+            sig[rb >> 1] |= live && fabsf(gval) >= eps;
+            float gz = live ? lam[cb] * gval * dcap : 0.f;
+            o[j] = (bf16)gz;
+            sl.GZT[gzt_off] = o[j];
+            gzt_off += (uint32_t)sl.Np;
+          }
+          uint2 packed;
+          __builtin_memcpy(&packed, o, 8);
+          *(uint2*)(sl.GZ + (gz_row + (uint32_t)vl)) = packed;
+        }
+      }
+    }
+    // block flags for the gradient filter (an OR, so the order of arrival is immaterial)
+    const bool any0 = __builtin_amdgcn_ballot_w64(sig[0]) != 0;
+    const bool any1 = __builtin_amdgcn_ballot_w64(sig[1]) != 0;
+    if (tc.lane == 0) {
+      const int vsteps = sl.vs / 64;
+      uint32_t* f_nv = sl.flags_nv + (int64_t)n_tile * vsteps + t * 4 + tc.wave_r * 2;
+      if (any0) atomicOr(f_nv, 1u);
+      if (any1) atomicOr(f_nv + 1, 1u);
+      if (any0 || any1) atomicOr(sl.flags_vn + (int64_t)t * (sl.Np / 64) + n_tile * 4 + tc.wave_c, 1u);
+    }
+  });
+}
+
+// ------------------------------------------------------------------ gradient products
+// out tile [256 d x 256 c]:  acc[d][c] = sum_k P[d][k] * Q[c][k],  k stepping over 64-wide
+// blocks; with FILTERED only the blocks whose flag (row tile_c of `flags`) is set.
+//   DC = false:  P = CT [D, vs], Q = GZ  [Np, vs], c = token      -> dEacc[c][d] (+)= acc
+//   DC = true :  P = ET [D, Np], Q = GZT [vs, Np], c = vocabulary -> dC[v0 + c][d] = bf16(acc)
+template <bool DC, bool FILTERED>
+__global__ __launch_bounds__(kThreads) void bwd_product_mfma_kernel(BwdCommon c, BwdMfmaSlab sl, bf16* out_dC) {
+  __shared__ __attribute__((aligned(1024))) char lds[kLdsBytes];
+  __shared__ uint16_t klist[kMaxKSteps];
+  __shared__ int kcount_s;
+  TileCoords tc;
+  tc.init();
+  const int tiles_r = (c.D + kTileR - 1) / kTileR;
+  const int tile_r = blockIdx.x % tiles_r, tile_c = blockIdx.x / tiles_r;
+  const int d0 = tile_r * kTileR, c0 = tile_c * kTileC;
+  const int K = DC ? sl.Np : sl.vs;
+  const int64_t ld_bytes = (int64_t)K * 2;
+  const char* P = (const char*)(DC ? sl.ET : sl.CT) + (int64_t)d0 * ld_bytes;
+  const char* Q = (const char*)(DC ? sl.GZT : sl.GZ) + (int64_t)c0 * ld_bytes;
+  const int ksteps = K / kTileK;
+
+  int kcount = ksteps;
+  if (FILTERED) {
+    const uint32_t* flags = (DC ? sl.flags_vn : sl.flags_nv) + (int64_t)tile_c * ksteps;
+    if (tc.wave == 0) {
+      int count = 0;
+      for (int base = 0; base < ksteps; base += 64) {
+        int idx = base + tc.lane;
+        bool on = idx < ksteps && flags[idx] != 0;
+        uint64_t mask = __builtin_amdgcn_ballot_w64(on);
+        int pos = count + __builtin_popcountll(mask & ((1ull << tc.lane) - 1ull));
+        if (on) klist[pos] = (uint16_t)idx;
+        count += __builtin_popcountll(mask);
+      }
+      if (tc.lane == 0) kcount_s = count;
+    }
+    __syncthreads();
+    kcount = __builtin_amdgcn_readfirstlane(kcount_s);
+  }
+
+  f32x16 acc[kRB][kCB];
+#pragma unroll
+  for (int rb = 0; rb < kRB; ++rb)
+#pragma unroll
+    for (int cb = 0; cb < kCB; ++cb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[rb][cb][i] = 0.f;
+
+  if (kcount > 0) {
+    uint32_t offP[4], offQ[4];
+    dma_offsets(tc, min(kTileR, c.D - d0), ld_bytes, offP);
+    dma_offsets(tc, kTileC, ld_bytes, offQ);     // Q rows are padded to full tiles in the workspace
+    const uint32_t lds_base = lds_addr(lds);
+    const uint32_t klist_addr = lds_addr(klist);
+    auto kstep_at = [&](int i) -> int {
+      if (!FILTERED) return i;
+      uint32_t v;
+      asm volatile("ds_read_u16 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(klist_addr + 2u * (uint32_t)i));
+      return __builtin_amdgcn_readfirstlane((int)v);
+    };
+    int64_t koff = (int64_t)kstep_at(0) * (kTileK * 2);
+    dma_slice(tc, P + koff, offP, lds);
+    dma_slice(tc, Q + koff, offQ, lds + kSliceBytes);
+    int stage = 0;
+    for (int i = 0; i < kcount; ++i) {
+      wait_dma();
+      __builtin_amdgcn_s_barrier();
+      if (i + 1 < kcount) {
+        koff = (int64_t)kstep_at(i + 1) * (kTileK * 2);
+        char* nxt = lds + (stage ^ 1) * kStageBytes;
+        dma_slice(tc, P + koff, offP, nxt);
+        dma_slice(tc, Q + koff, offQ, nxt + kSliceBytes);
+      }
+      mma_stage(tc, lds_base + stage * kStageBytes, acc);
+      stage ^= 1;
+    }
+  }
+
+#pragma unroll
+  for (int cb = 0; cb < kCB; ++cb) {
+    const int col = c0 + tc.wave_c * kWaveCols + cb * 32 + (tc.lane & 31);
+#pragma unroll
+    for (int rb = 0; rb < kRB; ++rb)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int d = d0 + tc.wave_r * kWaveRows + rb * 32 + 8 * g + 4 * (tc.lane >> 5);
+        if (d >= c.D) continue;
+        float4 v = make_float4(acc[rb][cb][g * 4 + 0], acc[rb][cb][g * 4 + 1], acc[rb][cb][g * 4 + 2],
+                               acc[rb][cb][g * 4 + 3]);
+        if (DC) {
+          const int vv = sl.v0 + col;
+          if (vv < c.V) {
+            bf16 o[4] = {(bf16)v.x, (bf16)v.y, (bf16)v.z, (bf16)v.w};
+            uint2 packed;
+            __builtin_memcpy(&packed, o, 8);
+            *(uint2*)(out_dC + (int64_t)vv * c.D + d) = packed;
+          }
+        } else if (col < c.N) {
+          float4* dst = (float4*)(sl.dEacc + (int64_t)col * c.D + d);
+          if (!sl.first) {
+            float4 old = *dst;
+            v.x += old.x; v.y += old.y; v.z += old.z; v.w += old.w;
+          }
+          *dst = v;
+        }
+      }
+  }
+}
+
+// counts the (256 token x 64 vocabulary) filter blocks of a slab and how many were kept
+__global__ void count_flags_kernel(const uint32_t* flags_nv, int n_tiles, int vsteps, int v0, int V,
+                                   FilterStats* stats) {
+  unsigned long long total = 0, kept = 0;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n_tiles * vsteps; i += gridDim.x * blockDim.x) {
+    int vstep = i % vsteps;
+    if (v0 + vstep * 64 < V) {
+      ++total;
+      kept += flags_nv[i] != 0;
+    }
+  }
+  for (int o = 32; o > 0; o >>= 1) {
+    total += __shfl_xor(total, o);
+    kept += __shfl_xor(kept, o);
+  }
+  if ((threadIdx.x & 63) == 0 && total) {
+    atomicAdd(&stats->blocks_total, total);   // integer sums: order-independent
+    atomicAdd(&stats->blocks_kept, kept);
+  }
+}
+
+__global__ void zero_u32_kernel(uint32_t* p, int64_t count) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  for (; i < count; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0u;
+}
+
+}  // namespace
+
+hipError_t launch_transpose_bf16(const bf16* in, int rows_valid, int rows_padded, int cols, int64_t ld_in,
+                                 bf16* out, hipStream_t stream) {
+  dim3 grid(rows_padded / 64, (cols + 63) / 64);
+  hipLaunchKernelGGL(transpose_bf16_kernel, grid, dim3(256), 0, stream, (const uint16_t*)in, rows_valid,
+                     rows_padded, cols, ld_in, (uint16_t*)out);
+  return hipGetLastError();
+}
+
+hipError_t launch_bwd_recompute_mfma(const BwdCommon& c, const BwdMfmaSlab& s, hipStream_t stream) {
+  const int n_tiles = s.Np / kTileC, v_tiles = s.vs / kTileR;
+  // clear the slab's flags
+  const int64_t nflags = (int64_t)n_tiles * (s.vs / 64) + (int64_t)v_tiles * (s.Np / 64);
+  // flags_nv and flags_vn are laid out back to back by the dispatcher
+  hipLaunchKernelGGL(zero_u32_kernel, dim3((unsigned)((nflags + 255) / 256)), dim3(256), 0, stream,
+                     s.flags_nv, nflags);
+  int splits = (256 + n_tiles - 1) / n_tiles;
+  if (splits > v_tiles) splits = v_tiles;
+  if (splits < 1) splits = 1;
+  int tps = (v_tiles + splits - 1) / splits;
+  splits = (v_tiles + tps - 1) / tps;
+  dim3 grid(n_tiles * splits);
+  if (c.softcap > 0.f)
+    hipLaunchKernelGGL(bwd_recompute_mfma_kernel<kCap>, grid, dim3(kThreads), 0, stream, c, s, splits, tps);
+  else
+    hipLaunchKernelGGL(bwd_recompute_mfma_kernel<kNoCap>, grid, dim3(kThreads), 0, stream, c, s, splits, tps);
+  hipLaunchKernelGGL(count_flags_kernel, dim3(8), dim3(256), 0, stream, s.flags_nv, n_tiles,
+                     s.vs / 64, s.v0, c.V, c.stats);
+  return hipGetLastError();
+}
+
+hipError_t launch_bwd_dE_mfma(const BwdCommon& c, const BwdMfmaSlab& s, hipStream_t stream) {
+  const int tiles_r = (c.D + kTileR - 1) / kTileR;
+  dim3 grid(tiles_r * (s.Np / kTileC));
+  if (c.filter_dE && c.eps > 0.f)
+    hipLaunchKernelGGL((bwd_product_mfma_kernel<false, true>), grid, dim3(kThreads), 0, stream, c, s, (bf16*)nullptr);
+  else
+    hipLaunchKernelGGL((bwd_product_mfma_kernel<false, false>), grid, dim3(kThreads), 0, stream, c, s, (bf16*)nullptr);
+  return hipGetLastError();
+}
+
+hipError_t launch_bwd_dC_mfma(const BwdCommon& c, const BwdMfmaSlab& s, void* out_dC, hipStream_t stream) {
+  const int tiles_r = (c.D + kTileR - 1) / kTileR;
+  dim3 grid(tiles_r * (s.vs / kTileC));
+  if (c.filter_dC && c.eps > 0.f)
+    hipLaunchKernelGGL((bwd_product_mfma_kernel<true, true>), grid, dim3(kThreads), 0, stream, c, s, (bf16*)out_dC);
+  else
+    hipLaunchKernelGGL((bwd_product_mfma_kernel<true, false>), grid, dim3(kThreads), 0, stream, c, s, (bf16*)out_dC);
+  return hipGetLastError();
+}
+
+}  // namespace cce

@@ -1,0 +1,409 @@
+// C ABI of the library (see include/cce.h): argument checks, path selection,
+// workspace carve-up and kernel sequencing.  No arithmetic of the method lives
+// here; every step of the path runs in the HIP kernels this file launches.
+#include "cce.h"
+#include "kernels.h"
+
+#include <hip/hip_runtime.h>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+
+namespace {
+
+using namespace cce;
+
+thread_local char g_hip_error[256] = "no HIP error recorded";
+
+int hip_fail(hipError_t e, const char* what) {
+  snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s", what, hipGetErrorString(e));
+  return CCE_EHIP;
+}
+#define CCE_HIP(call)                                 \
+  do {                                                \
+    hipError_t e_ = (call);                           \
+    if (e_ != hipSuccess) return hip_fail(e_, #call); \
+  } while (0)
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+constexpr int kMaxDevices = 64;
+constexpr int kXcds = 8;                 // MI355X: 8 accelerator complex dies, workgroups dealt round-robin
+constexpr int64_t kMfmaSlabCols = 8192;  // recommended backward slab width (vocabulary entries), MFMA path
+constexpr int64_t kPlainSlabCols = 4096;
+constexpr int kMaxFilteredKSteps = 2048;
+
+int cu_count() {
+  static int cached[kMaxDevices] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    cached[dev] = n;
+  }
+  return cached[dev];
+}
+
+// Library-owned workspace for the plain entry points: one buffer per device,
+// grown on demand, kept until the process ends.
+struct OwnedWorkspace {
+  void* ptr = nullptr;
+  size_t bytes = 0;
+};
+OwnedWorkspace g_owned[kMaxDevices];
+std::mutex g_owned_mutex;
+
+int owned_workspace(size_t need, void** out) {
+  int dev = 0;
+  CCE_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return CCE_EUNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_owned_mutex);
+  OwnedWorkspace& w = g_owned[dev];
+  if (w.bytes < need) {
+    if (w.ptr) {
+      CCE_HIP(hipDeviceSynchronize());   // earlier calls may still be using the old buffer
+      CCE_HIP(hipFree(w.ptr));
+      w.ptr = nullptr;
+      w.bytes = 0;
+    }
+    CCE_HIP(hipMalloc(&w.ptr, need));
+    w.bytes = need;
+  }
+  *out = w.ptr;
+  return CCE_OK;
+}
+
+bool use_mfma(int64_t D, const cce_opts* o) {
+  return o->dtype == CCE_BF16 && !(o->flags & CCE_PLAIN_KERNELS) && D % 64 == 0;
+}
+
+int check_common(const void* E, const void* C, const int64_t* targets, int64_t N, int64_t D, int64_t V,
+                 float softcap, const cce_opts* o) {
+  if (!o) return CCE_EINVAL;
+  if (o->dtype != CCE_BF16 && o->dtype != CCE_F32) return CCE_EUNSUPPORTED;
+  if (o->flags & ~(uint32_t)(CCE_FILTER_DE | CCE_FILTER_DC | CCE_VOCAB_SORT | CCE_PLAIN_KERNELS)) return CCE_EUNSUPPORTED;
+  if (o->flags & CCE_VOCAB_SORT) return CCE_EUNSUPPORTED;   // not built yet
+  if (!E || !C || !targets) return CCE_EINVAL;
+  if (N <= 0 || D <= 0 || V <= 0) return CCE_EINVAL;
+  if (N > (int64_t)0x7fff0000 || V > (int64_t)0x7fff0000 || D > (1 << 22)) return CCE_EINVAL;
+  if (!(softcap >= 0.f) || std::isinf(softcap)) return CCE_EINVAL;   // rejects NaN and negatives
+  if (!(o->filter_eps >= 0.f) || !(o->filter_eps < 1.f)) return CCE_EINVAL;
+  if (!aligned(E, 16) || !aligned(C, 16) || !aligned(targets, 8)) return CCE_EINVAL;
+  if (o->workspace && !aligned(o->workspace, 256)) return CCE_EINVAL;
+  return CCE_OK;
+}
+
+// ------------------------------------------------------------------ forward plan
+struct FwdPlan {
+  bool mfma;
+  int splits, tiles_per_split;
+  int n_tiles, v_tiles;
+  int wgs_per_xcd, group_n, group_s;
+  size_t partial_bytes;
+  size_t total_bytes;
+};
+
+FwdPlan plan_forward(int64_t N, int64_t D, int64_t V, const cce_opts* o) {
+  FwdPlan p{};
+  p.mfma = use_mfma(D, o);
+  const int tile = p.mfma ? 256 : 64;
+  const int cus = cu_count();
+  p.n_tiles = (int)((N + tile - 1) / tile);
+  p.v_tiles = (int)((V + tile - 1) / tile);
+  // enough vocabulary splits that one "round" of token tiles (at most 32 at a time on the
+  // MFMA path, so that the E tiles in flight stay cache resident) fills every CU
+  int round_tiles = p.mfma ? (p.n_tiles < 32 ? p.n_tiles : 32) : p.n_tiles;
+  int want = p.mfma ? cus : 4 * cus;
+  int splits = (want + round_tiles - 1) / round_tiles;
+  if (splits > p.v_tiles) splits = p.v_tiles;
+  if (splits < 1) splits = 1;
+  p.tiles_per_split = (p.v_tiles + splits - 1) / splits;
+  p.splits = (p.v_tiles + p.tiles_per_split - 1) / p.tiles_per_split;
+  if (p.mfma) {
+    const int total = p.n_tiles * p.splits;
+    p.wgs_per_xcd = (total + kXcds - 1) / kXcds;
+    // rectangle of (token tile, split) pairs handled side by side on one XCD
+    int gn = 1;
+    for (int g = 8; g >= 1; --g)
+      if (p.n_tiles % g == 0 && p.wgs_per_xcd % g == 0) { gn = g; break; }
+    int gs = 1;
+    for (int g = 32 / gn; g >= 1; --g)
+      if (p.splits % g == 0 && p.wgs_per_xcd % (gn * g) == 0) { gs = g; break; }
+    p.group_n = gn;
+    p.group_s = gs;
+  }
+  p.partial_bytes = align_up((size_t)p.splits * (size_t)N * sizeof(LsePartial), 256);
+  p.total_bytes = p.partial_bytes;
+  return p;
+}
+
+// ------------------------------------------------------------------ backward plan
+struct BwdPlan {
+  bool mfma;
+  int64_t Np, vs;          // padded token count, slab width
+  size_t off_flags, off_dEacc, off_ET, off_CT, off_GZ, off_GZT;
+  size_t total_bytes;
+};
+
+BwdPlan layout_backward(bool mfma, int64_t N, int64_t D, int64_t vs) {
+  BwdPlan p{};
+  p.mfma = mfma;
+  p.vs = vs;
+  size_t off = 256;   // FilterStats
+  if (mfma) {
+    p.Np = round_up(N, 256);
+    p.off_flags = off;
+    off += align_up(((size_t)(p.Np / 256) * (vs / 64) + (size_t)(vs / 256) * (p.Np / 64)) * 4, 256);
+    p.off_dEacc = off;
+    off += align_up((size_t)N * D * 4, 256);
+    p.off_ET = off;
+    off += align_up((size_t)D * p.Np * 2, 256);
+    p.off_CT = off;
+    off += align_up((size_t)D * vs * 2, 256);
+    p.off_GZ = off;
+    off += align_up((size_t)p.Np * vs * 2, 256);
+    p.off_GZT = off;
+    off += align_up((size_t)p.Np * vs * 2, 256);
+  } else {
+    p.Np = N;
+    p.off_flags = off;
+    off += align_up((size_t)((N + 63) / 64) * (vs / 64), 256);
+    p.off_dEacc = off;
+    off += align_up((size_t)N * D * 4, 256);
+    p.off_GZ = off;
+    off += align_up((size_t)N * vs * 4, 256);
+  }
+  p.total_bytes = off;
+  return p;
+}
+
+int64_t slab_tile(bool mfma) { return mfma ? 256 : 64; }
+
+int64_t recommended_slab(bool mfma, int64_t V) {
+  int64_t full = round_up(V, slab_tile(mfma));
+  int64_t rec = mfma ? kMfmaSlabCols : kPlainSlabCols;
+  return full < rec ? full : rec;
+}
+
+// widest slab (multiple of the tile width, at most the recommended one) that fits `bytes`
+int64_t fit_slab(bool mfma, int64_t N, int64_t D, int64_t V, size_t bytes) {
+  const int64_t t = slab_tile(mfma);
+  int64_t lo = 0, hi = recommended_slab(mfma, V) / t;   // in tiles
+  if (mfma) {
+    // the recompute kernel addresses the slab with 32-bit element offsets
+    const int64_t cap = (((int64_t)1 << 30) / round_up(N, 256)) / t;
+    if (hi > cap) hi = cap;
+  }
+  while (lo < hi) {
+    int64_t mid = (lo + hi + 1) / 2;
+    if (layout_backward(mfma, N, D, mid * t).total_bytes <= bytes) lo = mid; else hi = mid - 1;
+  }
+  return lo * t;
+}
+
+}  // namespace
+
+// =============================================================================
+extern "C" {
+
+void cce_default_opts(int dtype, cce_opts* opts) {
+  if (!opts) return;
+  memset(opts, 0, sizeof(*opts));
+  opts->dtype = dtype;
+  if (dtype == CCE_BF16) {
+    opts->flags = CCE_FILTER_DE | CCE_FILTER_DC;
+    opts->filter_eps = 0x1p-12f;
+  }
+}
+
+const char* cce_strerror(int status) {
+  switch (status) {
+    case CCE_OK: return "success";
+    case CCE_EINVAL: return "invalid argument (null or misaligned pointer, non-positive size, bad softcap or eps)";
+    case CCE_EWORKSPACE: return "workspace missing or too small (see cce_workspace_bytes)";
+    case CCE_EUNSUPPORTED: return "unsupported dtype or flag";
+    case CCE_EHIP: return g_hip_error;
+    default: return "unknown status";
+  }
+}
+
+size_t cce_workspace_bytes(int op, int64_t N, int64_t D, int64_t V, const cce_opts* opts) {
+  if (!opts || N <= 0 || D <= 0 || V <= 0) return 0;
+  if (opts->dtype != CCE_BF16 && opts->dtype != CCE_F32) return 0;
+  const bool mfma = use_mfma(D, opts);
+  switch (op) {
+    case CCE_OP_FORWARD: return plan_forward(N, D, V, opts).total_bytes;
+    case CCE_OP_BACKWARD: return layout_backward(mfma, N, D, recommended_slab(mfma, V)).total_bytes;
+    case CCE_OP_BACKWARD_MIN: return layout_backward(mfma, N, D, slab_tile(mfma)).total_bytes;
+    default: return 0;
+  }
+}
+
+void cce_filter_block(int64_t N, int64_t D, int64_t V, const cce_opts* opts, int* block_rows, int* block_cols) {
+  (void)N;
+  (void)V;
+  const bool mfma = opts && use_mfma(D, opts);
+  // MFMA path: dE skips (256 tokens x 64 vocab) blocks, dC skips (64 x 256); the
+  // common refinement 64 x 64 is what both tests see as "kept together".
+  if (block_rows) *block_rows = mfma ? 256 : 64;
+  if (block_cols) *block_cols = mfma ? 64 : 64;
+}
+
+int cce_forward_ex(const void* E, const void* C, const int64_t* targets, int64_t N, int64_t D, int64_t V,
+                   float softcap, int64_t ignore_index, float* out_loss, float* out_lse, const cce_opts* opts) {
+  int st = check_common(E, C, targets, N, D, V, softcap, opts);
+  if (st != CCE_OK) return st;
+  if (!out_loss || !out_lse) return CCE_EINVAL;
+  const FwdPlan plan = plan_forward(N, D, V, opts);
+  if (!opts->workspace || opts->workspace_bytes < plan.total_bytes) return CCE_EWORKSPACE;
+  hipStream_t stream = (hipStream_t)opts->stream;
+  LsePartial* partial = (LsePartial*)opts->workspace;
+
+  if (plan.mfma) {
+    FwdMfmaParams p{};
+    p.E = (const bf16*)E;
+    p.C = (const bf16*)C;
+    p.N = (int)N; p.D = (int)D; p.V = (int)V;
+    p.softcap = softcap;
+    p.partial = partial;
+    p.n_tiles = plan.n_tiles; p.v_tiles = plan.v_tiles;
+    p.splits = plan.splits; p.tiles_per_split = plan.tiles_per_split;
+    p.xcds = kXcds; p.wgs_per_xcd = plan.wgs_per_xcd;
+    p.group_n = plan.group_n; p.group_s = plan.group_s;
+    CCE_HIP(launch_fwd_lse_mfma(p, stream));
+  } else {
+    FwdPlainParams p{};
+    p.E = E; p.C = C; p.dtype = opts->dtype;
+    p.N = (int)N; p.D = (int)D; p.V = (int)V;
+    p.softcap = softcap;
+    p.partial = partial;
+    p.splits = plan.splits; p.tiles_per_split = plan.tiles_per_split;
+    CCE_HIP(launch_fwd_lse_plain(p, stream));
+  }
+  FinalizeParams f{};
+  f.E = E; f.C = C; f.dtype = opts->dtype; f.targets = targets;
+  f.N = (int)N; f.D = (int)D; f.V = (int)V;
+  f.softcap = softcap; f.ignore_index = ignore_index;
+  f.partial = partial; f.splits = plan.splits;
+  f.out_loss = out_loss; f.out_lse = out_lse;
+  CCE_HIP(launch_finalize(f, stream));
+  return CCE_OK;
+}
+
+int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_t N, int64_t D, int64_t V,
+                    float softcap, int64_t ignore_index, const float* lse, const float* dLoss, void* out_dE,
+                    void* out_dC, const cce_opts* opts) {
+  int st = check_common(E, C, targets, N, D, V, softcap, opts);
+  if (st != CCE_OK) return st;
+  if (!lse || !dLoss || !out_dE || !out_dC) return CCE_EINVAL;
+  if (!aligned(out_dE, 16) || !aligned(out_dC, 16)) return CCE_EINVAL;
+  const bool mfma = use_mfma(D, opts);
+  if (!opts->workspace) return CCE_EWORKSPACE;
+  const int64_t vs = fit_slab(mfma, N, D, V, opts->workspace_bytes);
+  if (vs <= 0) return CCE_EWORKSPACE;
+  const BwdPlan plan = layout_backward(mfma, N, D, vs);
+  hipStream_t stream = (hipStream_t)opts->stream;
+  char* ws = (char*)opts->workspace;
+
+  BwdCommon c{};
+  c.E = E; c.C = C; c.dtype = opts->dtype; c.targets = targets; c.lse = lse; c.dloss = dLoss;
+  c.N = (int)N; c.D = (int)D; c.V = (int)V;
+  c.softcap = softcap; c.ignore_index = ignore_index;
+  c.eps = opts->filter_eps;
+  c.filter_dE = (opts->flags & CCE_FILTER_DE) ? 1 : 0;
+  c.filter_dC = (opts->flags & CCE_FILTER_DC) ? 1 : 0;
+  c.stats = (FilterStats*)ws;
+  CCE_HIP(launch_clear_stats(c.stats, stream));
+  float* dEacc = (float*)(ws + plan.off_dEacc);
+
+  if (mfma) {
+    BwdMfmaSlab s{};
+    s.Np = (int)plan.Np;
+    s.ET = (bf16*)(ws + plan.off_ET);
+    s.CT = (bf16*)(ws + plan.off_CT);
+    s.GZ = (bf16*)(ws + plan.off_GZ);
+    s.GZT = (bf16*)(ws + plan.off_GZT);
+    s.dEacc = dEacc;
+    // a filtered contraction keeps its list of 64-wide steps in LDS; longer ones run unfiltered
+    if (plan.Np / 64 > kMaxFilteredKSteps) c.filter_dC = 0;
+    CCE_HIP(launch_transpose_bf16((const bf16*)E, (int)N, (int)plan.Np, (int)D, D, s.ET, stream));
+    for (int64_t v0 = 0; v0 < V; v0 += vs) {
+      const int64_t vs_this = (round_up(V - v0, 256) < vs) ? round_up(V - v0, 256) : vs;
+      s.v0 = (int)v0;
+      s.vs = (int)vs_this;
+      s.first = v0 == 0;
+      s.flags_nv = (uint32_t*)(ws + plan.off_flags);
+      s.flags_vn = s.flags_nv + (plan.Np / 256) * (vs_this / 64);
+      const int64_t rows_valid = (V - v0 < vs_this) ? V - v0 : vs_this;
+      CCE_HIP(launch_transpose_bf16((const bf16*)C + v0 * D, (int)rows_valid, (int)vs_this, (int)D, D, s.CT, stream));
+      CCE_HIP(launch_bwd_recompute_mfma(c, s, stream));
+      CCE_HIP(launch_bwd_dC_mfma(c, s, out_dC, stream));
+      CCE_HIP(launch_bwd_dE_mfma(c, s, stream));
+    }
+  } else {
+    BwdPlainSlab s{};
+    s.GZ = (float*)(ws + plan.off_GZ);
+    s.dEacc = dEacc;
+    s.flags = (uint8_t*)(ws + plan.off_flags);
+    for (int64_t v0 = 0; v0 < V; v0 += vs) {
+      const int64_t vs_this = (round_up(V - v0, 64) < vs) ? round_up(V - v0, 64) : vs;
+      s.v0 = (int)v0;
+      s.vs = (int)vs_this;
+      s.first = v0 == 0;
+      CCE_HIP(launch_bwd_gz_plain(c, s, stream));
+      CCE_HIP(launch_bwd_dC_plain(c, s, out_dC, stream));
+      CCE_HIP(launch_bwd_dE_plain(c, s, stream));
+    }
+  }
+  CCE_HIP(launch_store_dE(dEacc, out_dE, opts->dtype, N * D, stream));
+  return CCE_OK;
+}
+
+int cce_forward(const void* E, const void* C, const int64_t* targets, int64_t N, int64_t D, int64_t V,
+                float softcap, int64_t ignore_index, float* out_loss, float* out_lse) {
+  cce_opts o;
+  cce_default_opts(CCE_BF16, &o);
+  int st = check_common(E, C, targets, N, D, V, softcap, &o);
+  if (st != CCE_OK) return st;
+  o.workspace_bytes = cce_workspace_bytes(CCE_OP_FORWARD, N, D, V, &o);
+  st = owned_workspace(o.workspace_bytes, &o.workspace);
+  if (st != CCE_OK) return st;
+  return cce_forward_ex(E, C, targets, N, D, V, softcap, ignore_index, out_loss, out_lse, &o);
+}
+
+int cce_backward(const void* E, const void* C, const int64_t* targets, int64_t N, int64_t D, int64_t V,
+                 float softcap, int64_t ignore_index, const float* lse, const float* dLoss, void* out_dE,
+                 void* out_dC) {
+  cce_opts o;
+  cce_default_opts(CCE_BF16, &o);
+  int st = check_common(E, C, targets, N, D, V, softcap, &o);
+  if (st != CCE_OK) return st;
+  o.workspace_bytes = cce_workspace_bytes(CCE_OP_BACKWARD, N, D, V, &o);
+  st = owned_workspace(o.workspace_bytes, &o.workspace);
+  if (st != CCE_OK) return st;
+  return cce_backward_ex(E, C, targets, N, D, V, softcap, ignore_index, lse, dLoss, out_dE, out_dC, &o);
+}
+
+int cce_backward_filter_stats(const void* workspace, void* stream, uint64_t* blocks_total, uint64_t* blocks_kept) {
+  if (!blocks_total || !blocks_kept) return CCE_EINVAL;
+  if (!workspace) {
+    int dev = 0;
+    CCE_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return CCE_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_owned_mutex);
+    workspace = g_owned[dev].ptr;
+    if (!workspace) return CCE_EWORKSPACE;
+  }
+  FilterStats host{};
+  CCE_HIP(hipMemcpyAsync(&host, workspace, sizeof(host), hipMemcpyDeviceToHost, (hipStream_t)stream));
+  CCE_HIP(hipStreamSynchronize((hipStream_t)stream));
+  *blocks_total = host.blocks_total;
+  *blocks_kept = host.blocks_kept;
+  return CCE_OK;
+}
+
+}  // extern "C"

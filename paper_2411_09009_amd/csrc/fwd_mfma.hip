@@ -1,0 +1,194 @@
+// Forward linear-log-sum-exp on MFMA (paper Section 4.2, Alg. 2), gfx950.
+//
+// A workgroup owns 256 tokens and a contiguous range of 256-wide vocabulary
+// tiles.  For every vocabulary tile it forms the 256 x 256 logit tile in
+// registers (rows = vocabulary, columns = tokens, see mfma_tile.h), applies the
+// optional soft-cap, and folds the tile into a running (max, sum-exp) pair per
+// token that never leaves registers.  Where Alg. 2 merges blocks of one token
+// through a spin-lock on the global LSE vector, this kernel writes one
+// (max, sum) partial per token per vocabulary split and a second tiny kernel
+// merges them in a fixed order (bitwise reproducible).
+#include "kernels.h"
+#include "mfma_tile.h"
+
+namespace cce {
+
+// Soft-cap handling of the logit tile:
+//   kNoCap    a = z
+//   kCapFixed a = cap*tanh(z/cap) with cap <= 40: |a| <= cap, so cap itself serves as the
+//             reference "maximum" and no running maximum is tracked (2^(-2*cap*log2e) is
+//             still a normal float)
+//   kCapMax   a = cap*tanh(z/cap), running maximum tracked like kNoCap
+enum { kNoCap = 0, kCapFixed = 1, kCapMax = 2 };
+
+// Fold one finished logit tile (this lane's 4 x 2 blocks) into the running base-2
+// statistics m2 = max(a)*log2e and s = sum 2^(a*log2e - m2) of the lane's two token
+// columns, and clear the accumulators.  RAGGED masks vocabulary rows >= V.
+template <int MODE, bool RAGGED>
+__device__ inline void fold_tile(f32x16 (&acc)[kRB][kCB], float (&m2)[kCB], float (&s)[kCB], int lane,
+                                 int v_base, int V, float cap_scale, float cap_l2) {
+#pragma unroll
+  for (int cb = 0; cb < kCB; ++cb) {
+    if (MODE == kCapFixed) {
+      // a*log2e - cap*log2e = -2*cap_l2 / (1 + 2^(z*cap_scale))
+      float sum = 0.f;
+#pragma unroll
+      for (int rb = 0; rb < kRB; ++rb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          float e = __builtin_amdgcn_exp2f(acc[rb][cb][i] * cap_scale);
+          float r = __builtin_amdgcn_rcpf(1.f + e);
+          float t = __builtin_amdgcn_exp2f(-2.f * cap_l2 * r);
+          if (RAGGED && v_base + rb * 32 + acc_row(lane, i) >= V) t = 0.f;
+          sum += t;
+          acc[rb][cb][i] = 0.f;
+        }
+      s[cb] += sum;
+      m2[cb] = cap_l2;
+    } else if (MODE == kNoCap) {
+      float tmax = -INFINITY;
+#pragma unroll
+      for (int rb = 0; rb < kRB; ++rb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          if (RAGGED && v_base + rb * 32 + acc_row(lane, i) >= V) acc[rb][cb][i] = -INFINITY;
+          tmax = fmaxf(tmax, acc[rb][cb][i]);
+        }
+      const float m_new = fmaxf(m2[cb], tmax * kLog2e);
+      // a lane whose rows are all masked so far has m_new = -inf: subtract 0 instead, every
+      // term is then 2^(-inf) = 0 and no inf - inf arises
+      const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
+      float sum = 0.f;
+#pragma unroll
+      for (int rb = 0; rb < kRB; ++rb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          sum += __builtin_amdgcn_exp2f(fmaf(acc[rb][cb][i], kLog2e, -m_ref));
+          acc[rb][cb][i] = 0.f;
+        }
+      s[cb] = s[cb] * __builtin_amdgcn_exp2f(m2[cb] - m_ref) + sum;
+      m2[cb] = m_new;
+    } else {
+      float tmax = -INFINITY;
+#pragma unroll
+      for (int rb = 0; rb < kRB; ++rb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          float e = __builtin_amdgcn_exp2f(acc[rb][cb][i] * cap_scale);
+          float r = __builtin_amdgcn_rcpf(1.f + e);
+          float a2 = fmaf(-2.f * cap_l2, r, cap_l2);
+          if (RAGGED && v_base + rb * 32 + acc_row(lane, i) >= V) a2 = -INFINITY;
+          acc[rb][cb][i] = a2;
+          tmax = fmaxf(tmax, a2);
+        }
+      const float m_new = fmaxf(m2[cb], tmax);
+      const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
+      float sum = 0.f;
+#pragma unroll
+      for (int rb = 0; rb < kRB; ++rb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          sum += __builtin_amdgcn_exp2f(acc[rb][cb][i] - m_ref);
+          acc[rb][cb][i] = 0.f;
+        }
+      s[cb] = s[cb] * __builtin_amdgcn_exp2f(m2[cb] - m_ref) + sum;
+      m2[cb] = m_new;
+    }
+  }
+}
+
+template <int MODE, bool SORT>
+__global__ __launch_bounds__(kThreads) void fwd_lse_mfma_kernel(FwdMfmaParams p) {
+  __shared__ __attribute__((aligned(1024))) char lds[kLdsBytes];
+
+  TileCoords tc;
+  tc.init();
+
+  // Workgroups are dealt to the 8 XCDs round-robin.  Give each XCD a compact
+  // rectangle of (token tile, vocabulary split) pairs so that its L2 sees each
+  // E slice and each C slice from several workgroups at about the same time.
+  int wg = blockIdx.x;
+  int logical = (wg % p.xcds) * p.wgs_per_xcd + wg / p.xcds;
+  if (logical >= p.n_tiles * p.splits) return;
+  int n_tile, split;
+  {
+    int per_group = p.group_n * p.group_s;
+    int g = logical / per_group, w = logical % per_group;
+    int groups_n = p.n_tiles / p.group_n;
+    n_tile = (g % groups_n) * p.group_n + w % p.group_n;
+    split = (g / groups_n) * p.group_s + w / p.group_n;
+  }
+  const int vt0 = split * p.tiles_per_split;
+  const int vt1 = min(vt0 + p.tiles_per_split, p.v_tiles);
+  const int n0 = n_tile * kTileC;
+  const int64_t ld_bytes = (int64_t)p.D * 2;
+  const int KT = p.D / kTileK;
+
+  uint32_t offQ[4];
+  dma_offsets(tc, min(kTileC, p.N - n0), ld_bytes, offQ);
+  const char* gQ = (const char*)p.E + (int64_t)n0 * ld_bytes;
+
+  // running statistics, base-2 domain: m2 = max(a) * log2(e), s = sum 2^(a*log2e - m2)
+  float m2[kCB], s[kCB];
+#pragma unroll
+  for (int cb = 0; cb < kCB; ++cb) { m2[cb] = -INFINITY; s[cb] = 0.f; }
+
+  f32x16 acc[kRB][kCB];
+#pragma unroll
+  for (int rb = 0; rb < kRB; ++rb)
+#pragma unroll
+    for (int cb = 0; cb < kCB; ++cb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[rb][cb][i] = 0.f;
+
+  const float cap_scale = MODE != kNoCap ? 2.f * kLog2e / p.softcap : 0.f;   // exp(2z/cap) = 2^(z*cap_scale)
+  const float cap_l2 = MODE != kNoCap ? p.softcap * kLog2e : kLog2e;
+
+  sweep_tiles(tc, lds, (const char*)p.C, p.V, ld_bytes, vt0, vt1, gQ, offQ, KT, acc, [&](int vt) {
+    // fold the finished logit tile into the running (max, sum)
+    const int v_base = vt * kTileR + tc.wave_r * kWaveRows;
+    if ((vt + 1) * kTileR > p.V)
+      fold_tile<MODE, true>(acc, m2, s, tc.lane, v_base, p.V, cap_scale, cap_l2);
+    else
+      fold_tile<MODE, false>(acc, m2, s, tc.lane, v_base, p.V, cap_scale, cap_l2);
+  });
+
+  // ---- merge the two lane halves, then the two row-waves, and write the partial ----
+  __syncthreads();
+  float2* red = (float2*)lds;   // [2 row-waves][256 tokens]
+#pragma unroll
+  for (int cb = 0; cb < kCB; ++cb) {
+    float mo = __shfl_xor(m2[cb], 32);
+    float so = __shfl_xor(s[cb], 32);
+    float mn = fmaxf(m2[cb], mo);
+    float sn = (mn == -INFINITY) ? 0.f
+             : s[cb] * __builtin_amdgcn_exp2f(m2[cb] - mn) + so * __builtin_amdgcn_exp2f(mo - mn);   // 2^(-inf) = 0
+    if (tc.lane < 32) {
+      int col = tc.wave_c * kWaveCols + cb * 32 + tc.lane;
+      red[tc.wave_r * kTileC + col] = make_float2(mn, sn);
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x < kTileC) {
+    int col = threadIdx.x;
+    float2 a = red[col], b = red[kTileC + col];
+    float mn = fmaxf(a.x, b.x);
+    float sn = (mn == -INFINITY) ? 0.f
+             : a.y * __builtin_amdgcn_exp2f(a.x - mn) + b.y * __builtin_amdgcn_exp2f(b.x - mn);
+    int n = n0 + col;
+    if (n < p.N) p.partial[(int64_t)split * p.N + n] = make_float2(mn, sn);
+  }
+}
+
+hipError_t launch_fwd_lse_mfma(const FwdMfmaParams& p, hipStream_t stream) {
+  dim3 grid(p.xcds * p.wgs_per_xcd), block(kThreads);
+  if (p.softcap > 40.f)
+    hipLaunchKernelGGL((fwd_lse_mfma_kernel<kCapMax, false>), grid, block, 0, stream, p);
+  else if (p.softcap > 0.f)
+    hipLaunchKernelGGL((fwd_lse_mfma_kernel<kCapFixed, false>), grid, block, 0, stream, p);
+  else
+    hipLaunchKernelGGL((fwd_lse_mfma_kernel<kNoCap, false>), grid, block, 0, stream, p);
+  return hipGetLastError();
+}
+
+}  // namespace cce

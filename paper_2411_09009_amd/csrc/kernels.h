@@ -1,0 +1,119 @@
+// Internal launch interface between the C-ABI dispatcher and the HIP kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace cce {
+
+typedef __bf16 bf16;
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// Per-token forward partial: m2 = max_j(a_ij) * log2(e) over a vocabulary range,
+// s = sum_j 2^(a_ij * log2(e) - m2) over the same range.  Both kernel families
+// produce this pair and the finalize kernel merges them.
+typedef float2 LsePartial;
+
+// ---- forward, MFMA path ------------------------------------------------------
+struct FwdMfmaParams {
+  const bf16* E;        // [N, D]
+  const bf16* C;        // [V, D]
+  int N, D, V;
+  float softcap;        // 0 = none
+  LsePartial* partial;  // [splits, N]
+  int n_tiles, v_tiles; // ceil(N / 256), ceil(V / 256)
+  int splits, tiles_per_split;
+  int xcds, wgs_per_xcd;   // grid = xcds * wgs_per_xcd >= n_tiles * splits
+  int group_n, group_s;    // rectangle of (token tile, split) pairs an XCD works on
+};
+hipError_t launch_fwd_lse_mfma(const FwdMfmaParams& p, hipStream_t stream);
+
+// ---- forward, plain kernels (float or bf16 storage, fp32 FMA) -----------------
+struct FwdPlainParams {
+  const void* E;
+  const void* C;
+  int dtype;            // CCE_BF16 / CCE_F32
+  int N, D, V;
+  float softcap;
+  LsePartial* partial;  // [splits, N]
+  int splits, tiles_per_split;   // 64-wide vocabulary tiles
+};
+hipError_t launch_fwd_lse_plain(const FwdPlainParams& p, hipStream_t stream);
+
+// ---- finalize: merge partials, indexed dot product, loss (Alg. 1 + Eq. 4) -----
+struct FinalizeParams {
+  const void* E;
+  const void* C;
+  int dtype;
+  const int64_t* targets;
+  int N, D, V;
+  float softcap;
+  int64_t ignore_index;
+  const LsePartial* partial;
+  int splits;
+  float* out_loss;
+  float* out_lse;
+};
+hipError_t launch_finalize(const FinalizeParams& p, hipStream_t stream);
+
+// ---- backward -----------------------------------------------------------------
+// Filter counters kept at the start of the backward workspace.
+struct FilterStats {
+  unsigned long long blocks_total;
+  unsigned long long blocks_kept;
+};
+
+// One vocabulary slab [v0, v0 + vs) of the backward pass; vs is the slab's padded
+// width (a multiple of the path's tile width), columns >= V hold zeros.
+struct BwdCommon {
+  const void* E;
+  const void* C;
+  int dtype;
+  const int64_t* targets;
+  const float* lse;
+  const float* dloss;
+  int N, D, V;
+  float softcap;
+  int64_t ignore_index;
+  float eps;            // 0 = no filtering
+  int filter_dE, filter_dC;
+  FilterStats* stats;
+};
+
+// MFMA path buffers (bf16).  Np = N rounded up to 256.
+struct BwdMfmaSlab {
+  int v0, vs, Np;
+  bf16* ET;             // [D, Np]   E transposed, zero beyond N (filled once per call)
+  bf16* CT;             // [D, vs]   slab of C transposed, zero beyond V
+  bf16* GZ;             // [Np, vs]  dloss * G * a'   (token-major)
+  bf16* GZT;            // [vs, Np]  the same, vocabulary-major
+  float* dEacc;         // [N, D]
+  uint32_t* flags_nv;   // [Np/256, vs/64]  block (256 tokens x 64 vocab) has a significant entry
+  uint32_t* flags_vn;   // [vs/256, Np/64]  block (64 tokens x 256 vocab) has a significant entry;
+                        // starts right after flags_nv (the two are cleared as one array)
+  int first;            // first slab of the call: dEacc is overwritten instead of added to
+};
+hipError_t launch_transpose_bf16(const bf16* in, int rows_valid, int rows_padded, int cols, int64_t ld_in,
+                                 bf16* out, hipStream_t stream);
+hipError_t launch_bwd_recompute_mfma(const BwdCommon& c, const BwdMfmaSlab& s, hipStream_t stream);
+hipError_t launch_bwd_dE_mfma(const BwdCommon& c, const BwdMfmaSlab& s, hipStream_t stream);
+hipError_t launch_bwd_dC_mfma(const BwdCommon& c, const BwdMfmaSlab& s, void* out_dC, hipStream_t stream);
+
+// Plain path buffers (GZ kept in fp32, token-major only).
+struct BwdPlainSlab {
+  int v0, vs;           // vs multiple of 64
+  float* GZ;            // [N, vs]
+  float* dEacc;         // [N, D]
+  uint8_t* flags;       // [ceil(N/64), vs/64]
+  int first;
+};
+hipError_t launch_bwd_gz_plain(const BwdCommon& c, const BwdPlainSlab& s, hipStream_t stream);
+hipError_t launch_bwd_dE_plain(const BwdCommon& c, const BwdPlainSlab& s, hipStream_t stream);
+hipError_t launch_bwd_dC_plain(const BwdCommon& c, const BwdPlainSlab& s, void* out_dC, hipStream_t stream);
+
+// dEacc (fp32 [N, D]) -> out_dE in the storage dtype.
+hipError_t launch_store_dE(const float* dEacc, void* out_dE, int dtype, int64_t count, hipStream_t stream);
+hipError_t launch_clear_stats(FilterStats* stats, hipStream_t stream);
+
+}  // namespace cce

@@ -1,0 +1,114 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol include/cce.h declares, sizes its workspaces as documented and rejects bad
+arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2411_09009_amd as L
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "cce.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cce_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = L.load()
+    names = declared_symbols()
+    assert {"cce_forward", "cce_backward", "cce_forward_ex", "cce_backward_ex", "cce_workspace_bytes",
+            "cce_strerror", "cce_default_opts", "cce_filter_block", "cce_backward_filter_stats"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_binding_exposes_the_same_names():
+    for n in declared_symbols():
+        assert hasattr(L, n), n
+
+
+def test_default_opts_and_error_strings():
+    o = L.cce_default_opts(L.CCE_BF16)
+    assert o.flags == (L.CCE_FILTER_DE | L.CCE_FILTER_DC) and o.filter_eps == 2.0 ** -12
+    o = L.cce_default_opts(L.CCE_F32)
+    assert o.flags == 0 and o.filter_eps == 0.0
+    for st in (0, -1, -2, -3, -4, -99):
+        assert isinstance(L.cce_strerror(st), str) and L.cce_strerror(st)
+
+
+def test_forward_workspace_is_linear_in_tokens_and_independent_of_vocabulary():
+    o = L.cce_default_opts(L.CCE_BF16)
+    a = L.cce_workspace_bytes(L.CCE_OP_FORWARD, 8192, 2304, 256000, o)
+    b = L.cce_workspace_bytes(L.CCE_OP_FORWARD, 8192, 2304, 128000, o)
+    c = L.cce_workspace_bytes(L.CCE_OP_FORWARD, 16384, 2304, 256000, o)
+    assert a == b                          # no O(V) term
+    assert a <= 8192 * 8 * 8 + 256         # at most 8 (max, sum) pairs per token
+    assert c <= 2 * a + 256
+    logits_bytes = 8192 * 256000 * 4
+    assert a < logits_bytes / 10000
+
+
+def test_backward_workspace_is_bounded_by_the_slab_not_the_vocabulary():
+    o = L.cce_default_opts(L.CCE_BF16)
+    N, D = 8192, 2304
+    rec = L.cce_workspace_bytes(L.CCE_OP_BACKWARD, N, D, 256000, o)
+    rec2 = L.cce_workspace_bytes(L.CCE_OP_BACKWARD, N, D, 1024000, o)
+    mn = L.cce_workspace_bytes(L.CCE_OP_BACKWARD_MIN, N, D, 256000, o)
+    assert rec == rec2 and 0 < mn < rec
+    assert rec < N * 256000 * 2 / 8        # far below even a bf16 logit matrix
+    assert L.cce_workspace_bytes(99, N, D, 256000, o) == 0
+    assert L.cce_workspace_bytes(L.CCE_OP_FORWARD, 0, D, 256000, o) == 0
+
+
+def test_bad_arguments_are_rejected_without_a_gpu():
+    lib = L.load()
+    o = L.cce_default_opts(L.CCE_BF16)
+    buf = (ctypes.c_char * 4096)()
+    p = (ctypes.addressof(buf) + 255) // 256 * 256
+    args = dict(E=p, C=p, t=p, N=4, D=64, V=8, cap=0.0, ign=-100, loss=p, lse=p)
+
+    def fwd(**kw):
+        a = dict(args, **kw)
+        return lib.cce_forward_ex(a["E"], a["C"], a["t"], a["N"], a["D"], a["V"], a["cap"], a["ign"],
+                                  a["loss"], a["lse"], ctypes.byref(kw.get("opts", o)))
+    assert fwd(E=None) == -1
+    assert fwd(N=0) == -1 and fwd(V=-3) == -1 and fwd(D=0) == -1
+    assert fwd(cap=-1.0) == -1 and fwd(cap=float("nan")) == -1
+    assert fwd(E=p + 2) == -1                       # misaligned
+    assert fwd(loss=None) == -1
+    assert fwd() == -2                              # no workspace
+    bad = L.cce_default_opts(L.CCE_BF16)
+    bad.dtype = 7
+    assert fwd(opts=bad) == -3
+    bad = L.cce_default_opts(L.CCE_BF16)
+    bad.flags = 1 << 9
+    assert fwd(opts=bad) == -3
+    bad = L.cce_default_opts(L.CCE_BF16)
+    bad.filter_eps = -0.5
+    assert fwd(opts=bad) == -1
+    r = lib.cce_backward_ex(p, p, p, 4, 64, 8, 0.0, -100, None, p, p, p, ctypes.byref(o))
+    assert r == -1
+    r = lib.cce_backward_ex(p, p, p, 4, 64, 8, 0.0, -100, p, p, p, p, ctypes.byref(o))
+    assert r == -2
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    import paper_2411_09009_amd.binding as B
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", "/nonexistent/libcce.so")
+    with pytest.raises(FileNotFoundError):
+        B.load()
+
+
+def test_product_package_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2411_09009_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.replace("no CPU or eager", ""), (f, "mentions the oracle")
