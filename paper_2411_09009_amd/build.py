@@ -16,7 +16,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_DIR = os.path.join(HERE, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libcce.so")
-SOURCES = ["cce_api.hip", "plain_kernels.hip", "fwd_mfma.hip", "bwd_mfma.hip"]
+SOURCES = ["cce_api.hip", "plain_kernels.hip", "fwd_mfma.hip", "bwd_mfma.hip", "mfma_probe.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -211,30 +211,27 @@ __global__ __launch_bounds__(kThreads) void bwd_product_mfma_kernel(BwdCommon c,
     uint32_t offP[4], offQ[4];
     dma_offsets(tc, min(kTileR, c.D - d0), ld_bytes, offP);
     dma_offsets(tc, kTileC, ld_bytes, offQ);     // Q rows are padded to full tiles in the workspace
-    const uint32_t lds_base = lds_addr(lds);
     const uint32_t klist_addr = lds_addr(klist);
-    auto kstep_at = [&](int i) -> int {
-      if (!FILTERED) return i;
-      uint32_t v;
-      asm volatile("ds_read_u16 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(klist_addr + 2u * (uint32_t)i));
-      return __builtin_amdgcn_readfirstlane((int)v);
-    };
-    int64_t koff = (int64_t)kstep_at(0) * (kTileK * 2);
-    dma_slice(tc, P + koff, offP, lds);
-    dma_slice(tc, Q + koff, offQ, lds + kSliceBytes);
-    int stage = 0;
-    for (int i = 0; i < kcount; ++i) {
-      wait_dma();
-      __builtin_amdgcn_s_barrier();
-      if (i + 1 < kcount) {
-        koff = (int64_t)kstep_at(i + 1) * (kTileK * 2);
-        char* nxt = lds + (stage ^ 1) * kStageBytes;
-        dma_slice(tc, P + koff, offP, nxt);
-        dma_slice(tc, Q + koff, offQ, nxt + kSliceBytes);
-      }
-      mma_stage(tc, lds_base + stage * kStageBytes, acc);
-      stage ^= 1;
-    }
+    int cursor = 0;
+    mma_pipeline(
+        tc, lds, kcount, acc,
+        [&](StageSrc& src) {
+          int kstep = cursor;
+          if (FILTERED) {
+            // the list lives in LDS; read it past the compiler (it would otherwise wait for
+            // every direct load in flight before any LDS access it can see)
+            uint32_t v;
+            asm volatile("ds_read_u16 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(klist_addr + 2u * (uint32_t)cursor));
+            kstep = __builtin_amdgcn_readfirstlane((int)v);
+          }
+          if (cursor + 1 < kcount) ++cursor;   // past the end: surplus loads repeat the last step
+          const int64_t koff = (int64_t)kstep * (kTileK * 2);
+          src.gP = P + koff;
+          src.gQ = Q + koff;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) { src.offP[j] = offP[j]; src.offQ[j] = offQ[j]; }
+        },
+        [&](int) {});
   }
 
 #pragma unroll

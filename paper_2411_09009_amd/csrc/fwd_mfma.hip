@@ -118,6 +118,7 @@ __global__ __launch_bounds__(kThreads) void fwd_lse_mfma_kernel(FwdMfmaParams p)
     n_tile = (g % groups_n) * p.group_n + w % p.group_n;
     split = (g / groups_n) * p.group_s + w / p.group_n;
   }
+  if (n_tile >= p.n_tiles || split >= p.splits) return;   // never index past the partial buffer
   const int vt0 = split * p.tiles_per_split;
   const int vt1 = min(vt0 + p.tiles_per_split, p.v_tiles);
   const int n0 = n_tile * kTileC;

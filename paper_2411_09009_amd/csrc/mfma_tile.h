@@ -16,8 +16,12 @@
 // Operand K-slices (256 rows x 64 bf16 = 32 KB each) are brought in by
 // global_load_lds_dwordx4 straight into LDS, two stages deep (128 KB of the
 // CU's 160 KB).  A row of a K-slice is 128 B = 8 chunks of 16 B; chunk c of row
-// r is stored at chunk position c ^ (r & 7), so the 16-byte ds_read_b128 of 8
-// consecutive rows at one logical chunk touches all 8 chunk positions.  Because
+// r is stored at chunk position c ^ ((r >> 1) & 7).  The LDS has 64 banks of 4 B
+// and serves a ds_read_b128 sixteen lanes (256 B) per cycle; sixteen consecutive
+// rows at one logical chunk then cover all sixteen 16-byte bank groups (row parity
+// picks the 128-byte half, the swizzled chunk the position inside it), so the
+// fragment reads are conflict free.  (Measured: the 32-bank swizzle c ^ (r & 7)
+// costs one extra cycle per four on every read.)  Because
 // the LDS destination of a direct load is fixed (lane i of the instruction
 // writes bytes [16 i, 16 i + 16) of a 1 KB span), the swizzle is applied on the
 // global side: lane i fetches the chunk that belongs at its position.
@@ -79,7 +83,7 @@ struct TileCoords {
     wave_c = wave & 3;
     uint32_t p_row = (uint32_t)(wave_r * kWaveRows + (lane & 31)) * 128u;
     uint32_t q_row = (uint32_t)(wave_c * kWaveCols + (lane & 31)) * 128u + kSliceBytes;
-    uint32_t x = (uint32_t)((lane >> 5) ^ (lane & 7));
+    uint32_t x = (uint32_t)((lane >> 5) ^ ((lane >> 1) & 7));
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       uint32_t k = ((uint32_t)(ks * 2) ^ x) * 16u;
@@ -98,99 +102,161 @@ __device__ inline void dma_offsets(const TileCoords& tc, int rows_valid, int64_t
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     int r = (tc.wave * 4 + j) * 8 + (tc.lane >> 3);
-    int chunk = (tc.lane & 7) ^ (r & 7);
+    int chunk = (tc.lane & 7) ^ ((r >> 1) & 7);
     int rr = r < rows_valid ? r : rows_valid - 1;
     off[j] = (uint32_t)((int64_t)rr * ld_bytes + chunk * 16);
   }
 }
 
-// Issue the direct-to-LDS loads of one operand K-slice (this wave's share: 4 KB).
-// gbase is wave-uniform; lds_slice is the LDS address of the slice.
-__device__ inline void dma_slice(const TileCoords& tc, const char* gbase, const uint32_t (&off)[4],
-                                 char* lds_slice) {
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    __builtin_amdgcn_global_load_lds(CCE_GLOBAL_PTR(gbase + off[j]),
-                                     CCE_LDS_PTR(lds_slice + (tc.wave * 4 + j) * 1024), 16, 0, 0);
-  }
+// One direct-to-LDS load: this wave's j-th 1 KB span (8 rows) of a 32 KB operand
+// slice.  gbase is wave-uniform; lds_slice is the slice's LDS address.
+__device__ inline void dma_one(const TileCoords& tc, const char* gbase, uint32_t off, char* lds_slice, int j) {
+  __builtin_amdgcn_global_load_lds(CCE_GLOBAL_PTR(gbase + off), CCE_LDS_PTR(lds_slice + (tc.wave * 4 + j) * 1024), 16,
+                                   0, 0);
 }
 
-// One 64-deep stage of MFMA work.  `stage_addr` is the LDS address of the stage.
-// Fragments are double-buffered in registers: the reads of step ks+1 are in
-// flight while the 8 MFMAs of step ks execute.
-__device__ inline void mma_stage(const TileCoords& tc, uint32_t stage_addr, f32x16 (&acc)[kRB][kCB]) {
-  bf16x8 p[2][kRB], q[2][kCB];
-#define CCE_READ_FRAGS(buf, ks)                                              \
-  {                                                                          \
-    uint32_t pa = stage_addr + tc.p_off[ks], qa = stage_addr + tc.q_off[ks]; \
-    p[buf][0] = lds_read_b128<0>(pa);                                        \
-    p[buf][1] = lds_read_b128<4096>(pa);                                     \
-    p[buf][2] = lds_read_b128<8192>(pa);                                     \
-    p[buf][3] = lds_read_b128<12288>(pa);                                    \
-    q[buf][0] = lds_read_b128<0>(qa);                                        \
-    q[buf][1] = lds_read_b128<4096>(qa);                                     \
-  }
-  CCE_READ_FRAGS(0, 0)
-  lds_wait(p[0], q[0]);
+// Source of one 64-deep stage: wave-uniform base pointers of the P and Q K-slices
+// plus the per-lane row/chunk offsets from dma_offsets().
+struct StageSrc {
+  const char* gP;
+  const char* gQ;
+  uint32_t offP[4], offQ[4];
+};
+
+__device__ inline void dma_stage(const TileCoords& tc, const StageSrc& src, char* lds_stage) {
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) {
-    const int cur = ks & 1, nxt = cur ^ 1;
-    if (ks < 3) CCE_READ_FRAGS(nxt, ks + 1)
+  for (int j = 0; j < 4; ++j) dma_one(tc, src.gP, src.offP[j], lds_stage, j);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) dma_one(tc, src.gQ, src.offQ[j], lds_stage + kSliceBytes, j);
+}
+
+#define CCE_READ_FRAGS(buf, addr, ks)                                  \
+  {                                                                    \
+    uint32_t pa = (addr) + tc.p_off[ks], qa = (addr) + tc.q_off[ks];   \
+    p[buf][0] = lds_read_b128<0>(pa);                                  \
+    p[buf][1] = lds_read_b128<4096>(pa);                               \
+    p[buf][2] = lds_read_b128<8192>(pa);                               \
+    p[buf][3] = lds_read_b128<12288>(pa);                              \
+    q[buf][0] = lds_read_b128<0>(qa);                                  \
+    q[buf][1] = lds_read_b128<4096>(qa);                               \
+  }
+
+#define CCE_MMA8(buf)                                                                                          \
+  _Pragma("unroll") for (int rb = 0; rb < kRB; ++rb) _Pragma("unroll") for (int cb = 0; cb < kCB; ++cb)        \
+      acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p[buf][rb], q[buf][cb], acc[rb][cb], 0, 0, 0);
+
+// Software-pipelined main loop over `nsteps` 64-deep stages, two LDS stages.
+//
+//   next(src)      fills the DMA source of the following stage; it is called once per
+//                  stage, in stage order (a cursor that runs two stages ahead of the MFMAs).
+//   step_done(i)   is called after the MFMAs of stage i have been issued; an epilogue that
+//                  consumes the accumulators goes here (and must leave them zeroed).
+//
+// Per stage i the wave runs four 16-deep MFMA groups.  Fragments are double-buffered in
+// registers: the reads for group g+1 are in flight while group g multiplies.  The single
+// workgroup barrier of a stage sits between groups 2 and 3, after this wave's last LDS
+// read of stage i: past it (a) every wave's loads of stage i+1 have landed, so the first
+// fragments of stage i+1 are fetched under cover of group 3, and (b) stage i's buffer is
+// dead, so the loads of stage i+2 are issued into it, interleaved with group 3's MFMAs so
+// that their address-queue back-pressure never delays an MFMA.  Each load has one full
+// stage to arrive.
+template <class Next, class StepDone>
+__device__ inline void mma_pipeline(const TileCoords& tc, char* lds, int nsteps, f32x16 (&acc)[kRB][kCB], Next next,
+                                    StepDone step_done) {
+  if (nsteps <= 0) return;
+  const uint32_t lds_base = lds_addr(lds);
+  bf16x8 p[2][kRB], q[2][kCB];
+  StageSrc src;
+  next(src);
+  dma_stage(tc, src, lds);
+  wait_dma();
+  __builtin_amdgcn_s_barrier();
+  next(src);
+  dma_stage(tc, src, lds + kStageBytes);
+  CCE_READ_FRAGS(0, lds_base, 0)
+  lds_wait(p[0], q[0]);
+  int stage = 0;
+  // The loop body is branch free: the last two iterations fetch a stage nobody multiplies
+  // (next() keeps returning an in-bounds source) and prefetch fragments nobody uses.
+  for (int i = 0; i < nsteps; ++i) {
+    const uint32_t cur = lds_base + stage * kStageBytes;
+    const uint32_t oth = lds_base + (stage ^ 1) * kStageBytes;
+    CCE_READ_FRAGS(1, cur, 1)
+    CCE_MMA8(0)
+    __builtin_amdgcn_sched_barrier(0);
+    lds_wait(p[1], q[1]);
+    CCE_READ_FRAGS(0, cur, 2)
+    CCE_MMA8(1)
+    __builtin_amdgcn_sched_barrier(0);
+    lds_wait(p[0], q[0]);
+    CCE_READ_FRAGS(1, cur, 3)
+    CCE_MMA8(0)
+    __builtin_amdgcn_sched_barrier(0);
+    lds_wait(p[1], q[1]);
+    wait_dma();
+    __builtin_amdgcn_s_barrier();
+    CCE_READ_FRAGS(0, oth, 0)
+    next(src);
+    char* dst = lds + stage * kStageBytes;
+    // group 3 with the eight loads of stage i+2 slotted between its MFMAs
 #pragma unroll
     for (int rb = 0; rb < kRB; ++rb)
 #pragma unroll
-      for (int cb = 0; cb < kCB; ++cb)
-        acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p[cur][rb], q[cur][cb], acc[rb][cb], 0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
-    if (ks < 3) lds_wait(p[nxt], q[nxt]);
+      for (int cb = 0; cb < kCB; ++cb) {
+        acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p[1][rb], q[1][cb], acc[rb][cb], 0, 0, 0);
+        const int m = rb * kCB + cb;
+        if (m < 4) dma_one(tc, src.gP, src.offP[m], dst, m);
+        else dma_one(tc, src.gQ, src.offQ[m - 4], dst + kSliceBytes, m - 4);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    lds_wait(p[0], q[0]);
+    step_done(i);
+    stage ^= 1;
   }
-#undef CCE_READ_FRAGS
+  wait_dma();   // the surplus loads must have landed before the LDS is reused or released
 }
 
-// Sweep P tiles t0 .. t1-1 (tile t = rows [256 t, 256 t + 256) of P, clamped to
-// p_rows) against one fixed 256-row Q tile, with the K loop running seamlessly
-// from one tile into the next: the first stage of tile t+1 is already in flight
-// while the last stage of tile t is multiplied.  After the last stage of each
-// tile, on_tile(t) consumes the accumulators and must leave them zeroed.
-// One barrier per 64-deep stage: it publishes the stage that just landed and
-// retires the stage the next loads overwrite.
+// Sweep P tiles t0 .. t1-1 (tile t = rows [256 t, 256 t + 256) of P, clamped to p_rows)
+// against one fixed 256-row Q tile, with the K loop running seamlessly from one tile into
+// the next.  After the last stage of each tile, on_tile(t) consumes the accumulators and
+// must leave them zeroed.
 template <class OnTile>
 __device__ inline void sweep_tiles(const TileCoords& tc, char* lds, const char* P, int p_rows, int64_t ld_bytes,
                                    int t0, int t1, const char* gQ, const uint32_t (&offQ)[4], int KT,
                                    f32x16 (&acc)[kRB][kCB], OnTile on_tile) {
   if (t0 >= t1) return;
-  const uint32_t lds_base = lds_addr(lds);
-  uint32_t offP[4];
+  // DMA cursor: (tile, k-step) of the next stage to fetch
+  int cur_t = t0, cur_kt = 0;
   const char* gP = P + (int64_t)t0 * kTileR * ld_bytes;
+  uint32_t offP[4];
   dma_offsets(tc, min(kTileR, p_rows - t0 * kTileR), ld_bytes, offP);
-  dma_slice(tc, gP, offP, lds);
-  dma_slice(tc, gQ, offQ, lds + kSliceBytes);
-  int stage = 0;
-  for (int t = t0; t < t1; ++t) {
-    for (int kt = 0; kt < KT; ++kt) {
-      wait_dma();
-      __builtin_amdgcn_s_barrier();
-      bool more = true;
-      int64_t k_next = (int64_t)(kt + 1) * (kTileK * 2);
-      if (kt + 1 == KT) {
-        k_next = 0;
-        if (t + 1 < t1) {
-          gP += (int64_t)kTileR * ld_bytes;
-          dma_offsets(tc, min(kTileR, p_rows - (t + 1) * kTileR), ld_bytes, offP);
-        } else {
-          more = false;
+  int kt = 0, t = t0;   // compute cursor
+  mma_pipeline(
+      tc, lds, (t1 - t0) * KT, acc,
+      [&](StageSrc& src) {
+        const int64_t koff = (int64_t)cur_kt * (kTileK * 2);
+        src.gP = gP + koff;
+        src.gQ = gQ + koff;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { src.offP[j] = offP[j]; src.offQ[j] = offQ[j]; }
+        if (++cur_kt == KT) {
+          if (cur_t + 1 < t1) {
+            cur_kt = 0;
+            ++cur_t;
+            gP += (int64_t)kTileR * ld_bytes;
+            dma_offsets(tc, min(kTileR, p_rows - cur_t * kTileR), ld_bytes, offP);
+          } else {
+            cur_kt = KT - 1;   // past the end: keep re-fetching the last slice (surplus loads)
+          }
         }
-      }
-      if (more) {
-        char* nxt = lds + (stage ^ 1) * kStageBytes;
-        dma_slice(tc, gP + k_next, offP, nxt);
-        dma_slice(tc, gQ + k_next, offQ, nxt + kSliceBytes);
-      }
-      mma_stage(tc, lds_base + stage * kStageBytes, acc);
-      stage ^= 1;
-    }
-    on_tile(t);
-  }
+      },
+      [&](int) {
+        if (++kt == KT) {
+          kt = 0;
+          on_tile(t);
+          ++t;
+        }
+      });
 }
 
 // Row (0..31) inside a 32x32 block of accumulator element i of this lane.
