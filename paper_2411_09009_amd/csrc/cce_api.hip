@@ -77,6 +77,42 @@ int owned_workspace(size_t need, void** out) {
   return CCE_OK;
 }
 
+// Helper streams of the MFMA backward pass: the two gradient products of a vocabulary
+// slab run beside each other and beside the recompute of the next slab, so that the
+// partly filled last round of one kernel's workgroups is topped up by the others.
+// One set per device, created on first use; a call holds the device's mutex while it
+// enqueues, so the events are never recorded by two calls at once (a wait refers to
+// the record that precedes it in program order).
+constexpr int kEventRing = 4;
+struct Helpers {
+  std::mutex mutex;
+  bool ready = false;
+  hipStream_t product[2] = {};        // [0] dC products, [1] dE products
+  hipEvent_t recomputed[kEventRing] = {};
+  hipEvent_t dC_done[kEventRing] = {};
+  hipEvent_t dE_done[kEventRing] = {};
+};
+Helpers g_helpers[kMaxDevices];
+
+int helpers_for_device(Helpers** out) {
+  int dev = 0;
+  CCE_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return CCE_EUNSUPPORTED;
+  Helpers& h = g_helpers[dev];
+  std::lock_guard<std::mutex> lock(h.mutex);
+  if (!h.ready) {
+    for (auto& st : h.product) CCE_HIP(hipStreamCreateWithFlags(&st, hipStreamNonBlocking));
+    for (int i = 0; i < kEventRing; ++i) {
+      CCE_HIP(hipEventCreateWithFlags(&h.recomputed[i], hipEventDisableTiming));
+      CCE_HIP(hipEventCreateWithFlags(&h.dC_done[i], hipEventDisableTiming));
+      CCE_HIP(hipEventCreateWithFlags(&h.dE_done[i], hipEventDisableTiming));
+    }
+    h.ready = true;
+  }
+  *out = &h;
+  return CCE_OK;
+}
+
 bool use_mfma(int64_t D, const cce_opts* o) {
   return o->dtype == CCE_BF16 && !(o->flags & CCE_PLAIN_KERNELS) && D % 64 == 0;
 }
@@ -145,7 +181,7 @@ FwdPlan plan_forward(int64_t N, int64_t D, int64_t V, const cce_opts* o) {
 struct BwdPlan {
   bool mfma;
   int64_t Np, vs;          // padded token count, slab width
-  size_t off_flags, off_dEacc, off_ET, off_CT, off_GZ, off_GZT;
+  size_t off_flags[2], off_dEacc, off_ET, off_CT[2], off_GZ[2], off_GZT[2];   // [2]: even / odd slabs (MFMA path)
   size_t total_bytes;
 };
 
@@ -156,25 +192,27 @@ BwdPlan layout_backward(bool mfma, int64_t N, int64_t D, int64_t vs) {
   size_t off = 256;   // FilterStats
   if (mfma) {
     p.Np = round_up(N, 256);
-    p.off_flags = off;
-    off += align_up(((size_t)(p.Np / 256) * (vs / 64) + (size_t)(vs / 256) * (p.Np / 64)) * 4, 256);
     p.off_dEacc = off;
     off += align_up((size_t)N * D * 4, 256);
     p.off_ET = off;
     off += align_up((size_t)D * p.Np * 2, 256);
-    p.off_CT = off;
-    off += align_up((size_t)D * vs * 2, 256);
-    p.off_GZ = off;
-    off += align_up((size_t)p.Np * vs * 2, 256);
-    p.off_GZT = off;
-    off += align_up((size_t)p.Np * vs * 2, 256);
+    for (int b = 0; b < 2; ++b) {
+      p.off_flags[b] = off;
+      off += align_up(((size_t)(p.Np / 256) * (vs / 64) + (size_t)(vs / 256) * (p.Np / 64)) * 4, 256);
+      p.off_CT[b] = off;
+      off += align_up((size_t)D * vs * 2, 256);
+      p.off_GZ[b] = off;
+      off += align_up((size_t)p.Np * vs * 2, 256);
+      p.off_GZT[b] = off;
+      off += align_up((size_t)p.Np * vs * 2, 256);
+    }
   } else {
     p.Np = N;
-    p.off_flags = off;
+    p.off_flags[0] = off;
     off += align_up((size_t)((N + 63) / 64) * (vs / 64), 256);
     p.off_dEacc = off;
     off += align_up((size_t)N * D * 4, 256);
-    p.off_GZ = off;
+    p.off_GZ[0] = off;
     off += align_up((size_t)N * vs * 4, 256);
   }
   p.total_bytes = off;
@@ -321,34 +359,58 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
   float* dEacc = (float*)(ws + plan.off_dEacc);
 
   if (mfma) {
+    Helpers* h = nullptr;
+    st = helpers_for_device(&h);
+    if (st != CCE_OK) return st;
+    std::lock_guard<std::mutex> lock(h->mutex);
     BwdMfmaSlab s{};
     s.Np = (int)plan.Np;
     s.ET = (bf16*)(ws + plan.off_ET);
-    s.CT = (bf16*)(ws + plan.off_CT);
-    s.GZ = (bf16*)(ws + plan.off_GZ);
-    s.GZT = (bf16*)(ws + plan.off_GZT);
     s.dEacc = dEacc;
     // a filtered contraction keeps its list of 64-wide steps in LDS; longer ones run unfiltered
     if (plan.Np / 64 > kMaxFilteredKSteps) c.filter_dC = 0;
     CCE_HIP(launch_transpose_bf16((const bf16*)E, (int)N, (int)plan.Np, (int)D, D, s.ET, stream));
-    for (int64_t v0 = 0; v0 < V; v0 += vs) {
+    int64_t slab = 0;
+    for (int64_t v0 = 0; v0 < V; v0 += vs, ++slab) {
+      const int b = (int)(slab & 1), e = (int)(slab % kEventRing);
       const int64_t vs_this = (round_up(V - v0, 256) < vs) ? round_up(V - v0, 256) : vs;
       s.v0 = (int)v0;
       s.vs = (int)vs_this;
       s.first = v0 == 0;
-      s.flags_nv = (uint32_t*)(ws + plan.off_flags);
+      s.CT = (bf16*)(ws + plan.off_CT[b]);
+      s.GZ = (bf16*)(ws + plan.off_GZ[b]);
+      s.GZT = (bf16*)(ws + plan.off_GZT[b]);
+      s.flags_nv = (uint32_t*)(ws + plan.off_flags[b]);
       s.flags_vn = s.flags_nv + (plan.Np / 256) * (vs_this / 64);
+      if (slab >= 2) {
+        // this slab's buffers were last read by the products of slab - 2
+        const int e2 = (int)((slab - 2) % kEventRing);
+        CCE_HIP(hipStreamWaitEvent(stream, h->dC_done[e2], 0));
+        CCE_HIP(hipStreamWaitEvent(stream, h->dE_done[e2], 0));
+      }
       const int64_t rows_valid = (V - v0 < vs_this) ? V - v0 : vs_this;
       CCE_HIP(launch_transpose_bf16((const bf16*)C + v0 * D, (int)rows_valid, (int)vs_this, (int)D, D, s.CT, stream));
       CCE_HIP(launch_bwd_recompute_mfma(c, s, stream));
-      CCE_HIP(launch_bwd_dC_mfma(c, s, out_dC, stream));
-      CCE_HIP(launch_bwd_dE_mfma(c, s, stream));
+      CCE_HIP(hipEventRecord(h->recomputed[e], stream));
+      CCE_HIP(hipStreamWaitEvent(h->product[0], h->recomputed[e], 0));
+      CCE_HIP(launch_bwd_dC_mfma(c, s, out_dC, h->product[0]));
+      CCE_HIP(hipEventRecord(h->dC_done[e], h->product[0]));
+      // dEacc is read-modify-written slab after slab: stream order on product[1] keeps that sequence
+      CCE_HIP(hipStreamWaitEvent(h->product[1], h->recomputed[e], 0));
+      CCE_HIP(launch_bwd_dE_mfma(c, s, h->product[1]));
+      CCE_HIP(hipEventRecord(h->dE_done[e], h->product[1]));
     }
+    // join: the last record on each helper stream covers everything enqueued on it
+    const int e_last = (int)((slab - 1) % kEventRing);
+    CCE_HIP(hipStreamWaitEvent(stream, h->dC_done[e_last], 0));
+    CCE_HIP(hipStreamWaitEvent(stream, h->dE_done[e_last], 0));
+    CCE_HIP(launch_store_dE(dEacc, out_dE, opts->dtype, N * D, stream));
+    return CCE_OK;
   } else {
     BwdPlainSlab s{};
-    s.GZ = (float*)(ws + plan.off_GZ);
+    s.GZ = (float*)(ws + plan.off_GZ[0]);
     s.dEacc = dEacc;
-    s.flags = (uint8_t*)(ws + plan.off_flags);
+    s.flags = (uint8_t*)(ws + plan.off_flags[0]);
     for (int64_t v0 = 0; v0 < V; v0 += vs) {
       const int64_t vs_this = (round_up(V - v0, 64) < vs) ? round_up(V - v0, 64) : vs;
       s.v0 = (int)v0;

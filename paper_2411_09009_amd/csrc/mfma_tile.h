@@ -141,7 +141,17 @@ __device__ inline void dma_stage(const TileCoords& tc, const StageSrc& src, char
     q[buf][1] = lds_read_b128<4096>(qa);                               \
   }
 
+// Orders every MFMA that follows after the volatile asm statements that precede (the
+// fragment reads just issued): without it the compiler sinks the reads below the MFMAs
+// and folds the two fragment buffers into one set of registers, which leaves the LDS
+// latency exposed.
+__device__ inline void pin_acc(f32x16 (&acc)[kRB][kCB]) {
+  asm volatile("" : "+v"(acc[0][0]), "+v"(acc[0][1]), "+v"(acc[1][0]), "+v"(acc[1][1]), "+v"(acc[2][0]),
+               "+v"(acc[2][1]), "+v"(acc[3][0]), "+v"(acc[3][1]));
+}
+
 #define CCE_MMA8(buf)                                                                                          \
+  pin_acc(acc);                                                                                                \
   _Pragma("unroll") for (int rb = 0; rb < kRB; ++rb) _Pragma("unroll") for (int cb = 0; cb < kCB; ++cb)        \
       acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p[buf][rb], q[buf][cb], acc[rb][cb], 0, 0, 0);
 
