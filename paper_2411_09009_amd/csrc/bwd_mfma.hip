@@ -47,12 +47,13 @@ constexpr int kMaxKSteps = 2048;   // longest filtered contraction: 131072 / 64
 
 // ------------------------------------------------------------------ recompute + G
 template <int MODE>
-__global__ __launch_bounds__(kThreads) void bwd_recompute_mfma_kernel(BwdCommon c, BwdMfmaSlab sl, int splits,
+__global__ __launch_bounds__(kThreads) void bwd_recompute_mfma_kernel(BwdCommon c, BwdMfmaSlab sl, XcdMap map,
                                                                       int tiles_per_split) {
   __shared__ __attribute__((aligned(1024))) char lds[kLdsBytes];
   TileCoords tc;
   tc.init();
-  const int n_tile = blockIdx.x / splits, split = blockIdx.x % splits;
+  int n_tile, split;
+  if (!xcd_map_decode(map, blockIdx.x, n_tile, split)) return;
   const int v_tiles = sl.vs / kTileR;
   const int t0 = split * tiles_per_split, t1 = min(t0 + tiles_per_split, v_tiles);
   const int n0 = n_tile * kTileC;
@@ -165,14 +166,15 @@ __global__ __launch_bounds__(kThreads) void bwd_recompute_mfma_kernel(BwdCommon 
 //   DC = false:  P = CT [D, vs], Q = GZ  [Np, vs], c = token      -> dEacc[c][d] (+)= acc
 //   DC = true :  P = ET [D, Np], Q = GZT [vs, Np], c = vocabulary -> dC[v0 + c][d] = bf16(acc)
 template <bool DC, bool FILTERED>
-__global__ __launch_bounds__(kThreads) void bwd_product_mfma_kernel(BwdCommon c, BwdMfmaSlab sl, bf16* out_dC) {
+__global__ __launch_bounds__(kThreads) void bwd_product_mfma_kernel(BwdCommon c, BwdMfmaSlab sl, bf16* out_dC,
+                                                                    XcdMap map) {
   __shared__ __attribute__((aligned(1024))) char lds[kLdsBytes];
   __shared__ uint16_t klist[kMaxKSteps];
   __shared__ int kcount_s;
   TileCoords tc;
   tc.init();
-  const int tiles_r = (c.D + kTileR - 1) / kTileR;
-  const int tile_r = blockIdx.x % tiles_r, tile_c = blockIdx.x / tiles_r;
+  int tile_r, tile_c;   // a = 256-wide slice of D, b = token tile (dE) or vocabulary tile (dC)
+  if (!xcd_map_decode(map, blockIdx.x, tile_r, tile_c)) return;
   const int d0 = tile_r * kTileR, c0 = tile_c * kTileC;
   const int K = DC ? sl.Np : sl.vs;
   const int64_t ld_bytes = (int64_t)K * 2;
@@ -313,11 +315,12 @@ hipError_t launch_bwd_recompute_mfma(const BwdCommon& c, const BwdMfmaSlab& s, h
   if (splits < 1) splits = 1;
   int tps = (v_tiles + splits - 1) / splits;
   splits = (v_tiles + tps - 1) / tps;
-  dim3 grid(n_tiles * splits);
+  const XcdMap map = make_xcd_map(n_tiles, splits);
+  dim3 grid(xcd_map_grid(map));
   if (c.softcap > 0.f)
-    hipLaunchKernelGGL(bwd_recompute_mfma_kernel<kCap>, grid, dim3(kThreads), 0, stream, c, s, splits, tps);
+    hipLaunchKernelGGL(bwd_recompute_mfma_kernel<kCap>, grid, dim3(kThreads), 0, stream, c, s, map, tps);
   else
-    hipLaunchKernelGGL(bwd_recompute_mfma_kernel<kNoCap>, grid, dim3(kThreads), 0, stream, c, s, splits, tps);
+    hipLaunchKernelGGL(bwd_recompute_mfma_kernel<kNoCap>, grid, dim3(kThreads), 0, stream, c, s, map, tps);
   hipLaunchKernelGGL(count_flags_kernel, dim3(8), dim3(256), 0, stream, s.flags_nv, n_tiles,
                      s.vs / 64, s.v0, c.V, c.stats);
   return hipGetLastError();
@@ -325,21 +328,23 @@ hipError_t launch_bwd_recompute_mfma(const BwdCommon& c, const BwdMfmaSlab& s, h
 
 hipError_t launch_bwd_dE_mfma(const BwdCommon& c, const BwdMfmaSlab& s, hipStream_t stream) {
   const int tiles_r = (c.D + kTileR - 1) / kTileR;
-  dim3 grid(tiles_r * (s.Np / kTileC));
+  const XcdMap map = make_xcd_map(tiles_r, s.Np / kTileC);
+  dim3 grid(xcd_map_grid(map));
   if (c.filter_dE && c.eps > 0.f)
-    hipLaunchKernelGGL((bwd_product_mfma_kernel<false, true>), grid, dim3(kThreads), 0, stream, c, s, (bf16*)nullptr);
+    hipLaunchKernelGGL((bwd_product_mfma_kernel<false, true>), grid, dim3(kThreads), 0, stream, c, s, (bf16*)nullptr, map);
   else
-    hipLaunchKernelGGL((bwd_product_mfma_kernel<false, false>), grid, dim3(kThreads), 0, stream, c, s, (bf16*)nullptr);
+    hipLaunchKernelGGL((bwd_product_mfma_kernel<false, false>), grid, dim3(kThreads), 0, stream, c, s, (bf16*)nullptr, map);
   return hipGetLastError();
 }
 
 hipError_t launch_bwd_dC_mfma(const BwdCommon& c, const BwdMfmaSlab& s, void* out_dC, hipStream_t stream) {
   const int tiles_r = (c.D + kTileR - 1) / kTileR;
-  dim3 grid(tiles_r * (s.vs / kTileC));
+  const XcdMap map = make_xcd_map(tiles_r, s.vs / kTileC);
+  dim3 grid(xcd_map_grid(map));
   if (c.filter_dC && c.eps > 0.f)
-    hipLaunchKernelGGL((bwd_product_mfma_kernel<true, true>), grid, dim3(kThreads), 0, stream, c, s, (bf16*)out_dC);
+    hipLaunchKernelGGL((bwd_product_mfma_kernel<true, true>), grid, dim3(kThreads), 0, stream, c, s, (bf16*)out_dC, map);
   else
-    hipLaunchKernelGGL((bwd_product_mfma_kernel<true, false>), grid, dim3(kThreads), 0, stream, c, s, (bf16*)out_dC);
+    hipLaunchKernelGGL((bwd_product_mfma_kernel<true, false>), grid, dim3(kThreads), 0, stream, c, s, (bf16*)out_dC, map);
   return hipGetLastError();
 }
 

@@ -31,7 +31,6 @@ inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
 constexpr int kMaxDevices = 64;
-constexpr int kXcds = 8;                 // MI355X: 8 accelerator complex dies, workgroups dealt round-robin
 constexpr int64_t kMfmaSlabCols = 8192;  // recommended backward slab width (vocabulary entries), MFMA path
 constexpr int64_t kPlainSlabCols = 4096;
 constexpr int kMaxFilteredKSteps = 2048;
@@ -88,6 +87,7 @@ struct Helpers {
   std::mutex mutex;
   bool ready = false;
   hipStream_t product[2] = {};        // [0] dC products, [1] dE products
+  hipEvent_t started = nullptr;
   hipEvent_t recomputed[kEventRing] = {};
   hipEvent_t dC_done[kEventRing] = {};
   hipEvent_t dE_done[kEventRing] = {};
@@ -102,6 +102,7 @@ int helpers_for_device(Helpers** out) {
   std::lock_guard<std::mutex> lock(h.mutex);
   if (!h.ready) {
     for (auto& st : h.product) CCE_HIP(hipStreamCreateWithFlags(&st, hipStreamNonBlocking));
+    CCE_HIP(hipEventCreateWithFlags(&h.started, hipEventDisableTiming));
     for (int i = 0; i < kEventRing; ++i) {
       CCE_HIP(hipEventCreateWithFlags(&h.recomputed[i], hipEventDisableTiming));
       CCE_HIP(hipEventCreateWithFlags(&h.dC_done[i], hipEventDisableTiming));
@@ -138,7 +139,6 @@ struct FwdPlan {
   bool mfma;
   int splits, tiles_per_split;
   int n_tiles, v_tiles;
-  int wgs_per_xcd, group_n, group_s;
   size_t partial_bytes;
   size_t total_bytes;
 };
@@ -159,19 +159,6 @@ FwdPlan plan_forward(int64_t N, int64_t D, int64_t V, const cce_opts* o) {
   if (splits < 1) splits = 1;
   p.tiles_per_split = (p.v_tiles + splits - 1) / splits;
   p.splits = (p.v_tiles + p.tiles_per_split - 1) / p.tiles_per_split;
-  if (p.mfma) {
-    const int total = p.n_tiles * p.splits;
-    p.wgs_per_xcd = (total + kXcds - 1) / kXcds;
-    // rectangle of (token tile, split) pairs handled side by side on one XCD
-    int gn = 1;
-    for (int g = 8; g >= 1; --g)
-      if (p.n_tiles % g == 0 && p.wgs_per_xcd % g == 0) { gn = g; break; }
-    int gs = 1;
-    for (int g = 32 / gn; g >= 1; --g)
-      if (p.splits % g == 0 && p.wgs_per_xcd % (gn * g) == 0) { gs = g; break; }
-    p.group_n = gn;
-    p.group_s = gs;
-  }
   p.partial_bytes = align_up((size_t)p.splits * (size_t)N * sizeof(LsePartial), 256);
   p.total_bytes = p.partial_bytes;
   return p;
@@ -310,8 +297,7 @@ int cce_forward_ex(const void* E, const void* C, const int64_t* targets, int64_t
     p.partial = partial;
     p.n_tiles = plan.n_tiles; p.v_tiles = plan.v_tiles;
     p.splits = plan.splits; p.tiles_per_split = plan.tiles_per_split;
-    p.xcds = kXcds; p.wgs_per_xcd = plan.wgs_per_xcd;
-    p.group_n = plan.group_n; p.group_s = plan.group_s;
+    p.map = make_xcd_map(plan.n_tiles, plan.splits);
     CCE_HIP(launch_fwd_lse_mfma(p, stream));
   } else {
     FwdPlainParams p{};
@@ -369,6 +355,8 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
     s.dEacc = dEacc;
     // a filtered contraction keeps its list of 64-wide steps in LDS; longer ones run unfiltered
     if (plan.Np / 64 > kMaxFilteredKSteps) c.filter_dC = 0;
+    // helper work may not start before the caller's earlier work on `stream` (which may produce C)
+    CCE_HIP(hipEventRecord(h->started, stream));
     CCE_HIP(launch_transpose_bf16((const bf16*)E, (int)N, (int)plan.Np, (int)D, D, s.ET, stream));
     int64_t slab = 0;
     for (int64_t v0 = 0; v0 < V; v0 += vs, ++slab) {
@@ -388,14 +376,19 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
         CCE_HIP(hipStreamWaitEvent(stream, h->dC_done[e2], 0));
         CCE_HIP(hipStreamWaitEvent(stream, h->dE_done[e2], 0));
       }
-      const int64_t rows_valid = (V - v0 < vs_this) ? V - v0 : vs_this;
-      CCE_HIP(launch_transpose_bf16((const bf16*)C + v0 * D, (int)rows_valid, (int)vs_this, (int)D, D, s.CT, stream));
       CCE_HIP(launch_bwd_recompute_mfma(c, s, stream));
       CCE_HIP(hipEventRecord(h->recomputed[e], stream));
       CCE_HIP(hipStreamWaitEvent(h->product[0], h->recomputed[e], 0));
       CCE_HIP(launch_bwd_dC_mfma(c, s, out_dC, h->product[0]));
       CCE_HIP(hipEventRecord(h->dC_done[e], h->product[0]));
-      // dEacc is read-modify-written slab after slab: stream order on product[1] keeps that sequence
+      // The transposed C slab is needed by the dE product only, so it is made on that
+      // product's stream, ahead of the recompute it would otherwise delay (its buffer was
+      // last read by the dE product of slab - 2, earlier on the same stream).  dEacc is
+      // read-modify-written slab after slab: stream order keeps that sequence.
+      if (slab == 0) CCE_HIP(hipStreamWaitEvent(h->product[1], h->started, 0));
+      const int64_t rows_valid = (V - v0 < vs_this) ? V - v0 : vs_this;
+      CCE_HIP(launch_transpose_bf16((const bf16*)C + v0 * D, (int)rows_valid, (int)vs_this, (int)D, D, s.CT,
+                                    h->product[1]));
       CCE_HIP(hipStreamWaitEvent(h->product[1], h->recomputed[e], 0));
       CCE_HIP(launch_bwd_dE_mfma(c, s, h->product[1]));
       CCE_HIP(hipEventRecord(h->dE_done[e], h->product[1]));

@@ -104,21 +104,10 @@ __global__ __launch_bounds__(kThreads) void fwd_lse_mfma_kernel(FwdMfmaParams p)
   TileCoords tc;
   tc.init();
 
-  // Workgroups are dealt to the 8 XCDs round-robin.  Give each XCD a compact
-  // rectangle of (token tile, vocabulary split) pairs so that its L2 sees each
-  // E slice and each C slice from several workgroups at about the same time.
-  int wg = blockIdx.x;
-  int logical = (wg % p.xcds) * p.wgs_per_xcd + wg / p.xcds;
-  if (logical >= p.n_tiles * p.splits) return;
+  // each XCD works on a compact rectangle of (token tile, vocabulary split) pairs, so that
+  // its L2 sees every E slice and C slice from several workgroups at about the same time
   int n_tile, split;
-  {
-    int per_group = p.group_n * p.group_s;
-    int g = logical / per_group, w = logical % per_group;
-    int groups_n = p.n_tiles / p.group_n;
-    n_tile = (g % groups_n) * p.group_n + w % p.group_n;
-    split = (g / groups_n) * p.group_s + w / p.group_n;
-  }
-  if (n_tile >= p.n_tiles || split >= p.splits) return;   // never index past the partial buffer
+  if (!xcd_map_decode(p.map, blockIdx.x, n_tile, split)) return;
   const int vt0 = split * p.tiles_per_split;
   const int vt1 = min(vt0 + p.tiles_per_split, p.v_tiles);
   const int n0 = n_tile * kTileC;
@@ -182,7 +171,7 @@ __global__ __launch_bounds__(kThreads) void fwd_lse_mfma_kernel(FwdMfmaParams p)
 }
 
 hipError_t launch_fwd_lse_mfma(const FwdMfmaParams& p, hipStream_t stream) {
-  dim3 grid(p.xcds * p.wgs_per_xcd), block(kThreads);
+  dim3 grid(xcd_map_grid(p.map)), block(kThreads);
   if (p.softcap > 40.f)
     hipLaunchKernelGGL((fwd_lse_mfma_kernel<kCapMax, false>), grid, block, 0, stream, p);
   else if (p.softcap > 0.f)

@@ -15,6 +15,40 @@ constexpr float kLn2 = 0.6931471805599453f;
 // produce this pair and the finalize kernel merges them.
 typedef float2 LsePartial;
 
+// Placement of a dim_a x dim_b grid of work items on the chip's XCDs (each has its own
+// L2).  The hardware deals workgroups to the XCDs round-robin, so workgroup wg runs on
+// XCD wg % 8.  The map hands every XCD a run of `wgs_per_xcd` consecutive logical items,
+// ordered as rectangles of group_a x group_b items (a fastest inside a rectangle,
+// rectangles a-major), so that the workgroups resident on one XCD at a time share as
+// many operand slices as possible.  group_a divides dim_a, group_b divides dim_b and
+// group_a * group_b divides wgs_per_xcd.
+constexpr int kXcds = 8;
+struct XcdMap {
+  int dim_a, dim_b, wgs_per_xcd, group_a, group_b;
+};
+inline XcdMap make_xcd_map(int dim_a, int dim_b) {
+  XcdMap m{dim_a, dim_b, 1, 1, 1};
+  const int total = dim_a * dim_b;
+  m.wgs_per_xcd = (total + kXcds - 1) / kXcds;
+  for (int g = 8; g >= 1; --g)
+    if (dim_a % g == 0 && m.wgs_per_xcd % g == 0) { m.group_a = g; break; }
+  for (int g = 32 / m.group_a; g >= 1; --g)
+    if (dim_b % g == 0 && m.wgs_per_xcd % (m.group_a * g) == 0) { m.group_b = g; break; }
+  return m;
+}
+inline unsigned xcd_map_grid(const XcdMap& m) { return (unsigned)(kXcds * m.wgs_per_xcd); }
+// false: this workgroup is padding (the grid is rounded up to a multiple of 8)
+__device__ inline bool xcd_map_decode(const XcdMap& m, int wg, int& a, int& b) {
+  const int logical = (wg % kXcds) * m.wgs_per_xcd + wg / kXcds;
+  if (logical >= m.dim_a * m.dim_b) return false;
+  const int per_group = m.group_a * m.group_b;
+  const int g = logical / per_group, w = logical % per_group;
+  const int groups_a = m.dim_a / m.group_a;
+  a = (g % groups_a) * m.group_a + w % m.group_a;
+  b = (g / groups_a) * m.group_b + w / m.group_a;
+  return a < m.dim_a && b < m.dim_b;
+}
+
 // ---- forward, MFMA path ------------------------------------------------------
 struct FwdMfmaParams {
   const bf16* E;        // [N, D]
@@ -24,8 +58,7 @@ struct FwdMfmaParams {
   LsePartial* partial;  // [splits, N]
   int n_tiles, v_tiles; // ceil(N / 256), ceil(V / 256)
   int splits, tiles_per_split;
-  int xcds, wgs_per_xcd;   // grid = xcds * wgs_per_xcd >= n_tiles * splits
-  int group_n, group_s;    // rectangle of (token tile, split) pairs an XCD works on
+  XcdMap map;              // a = token tile, b = vocabulary split
 };
 hipError_t launch_fwd_lse_mfma(const FwdMfmaParams& p, hipStream_t stream);
 
