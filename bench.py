@@ -22,6 +22,12 @@ if ROOT not in sys.path:
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16, vendor figure (no sparsity)
 
+# HBM bytes one launch of fwd_lse_mfma_kernel moves at the Gemma-2-2B shape, from the
+# rocprofv3 --pmc runs summarised in profiles/bench_gemma2_2b_hbm_traffic.md
+# (FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter reads for
+# cce_probe_copy of 1 GiB).  None for other workloads.
+MEASURED_FWD_TRAFFIC_BYTES = {"gemma2_2b": 20405.9e6 + 107.8e6}
+
 
 def cpu_baseline(w, rows):
     """The oracle as it stands, forward + backward, on the first `rows` tokens."""
@@ -50,7 +56,7 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="gemma2_2b")
-    ap.add_argument("--cpu-rows", type=int, default=192)
+    ap.add_argument("--cpu-rows", type=int, default=1536)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -91,6 +97,25 @@ def main():
 
     def bwd(o):
         L.cce_backward_ex(E, C, tg, lse, dloss, w.softcap, w.ignore_index, o, out_dE=dE, out_dC=dC)
+
+    # known-size copy (1 GiB): the reference a --pmc profile of this command scales its
+    # FETCH_SIZE / WRITE_SIZE readings by
+    cal_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    cal_dst = torch.empty_like(cal_src)
+    L.cce_probe_copy(cal_dst, cal_src)
+    del cal_src, cal_dst
+
+    # attainable MFMA rate on this machine: register-resident loop on N(0,1) x N(0,0.02) operands
+    fr = torch.cat([torch.randn(256 * 8, device=dev), 0.02 * torch.randn(128 * 8, device=dev)]).to(torch.bfloat16)
+    pout = torch.empty(512 * 512, dtype=torch.float32, device=dev)
+    L.cce_probe_mfma(fr, pout, 512, 2000)
+    torch.cuda.synchronize()
+    p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    p0.record()
+    L.cce_probe_mfma(fr, pout, 512, 20000)
+    p1.record()
+    torch.cuda.synchronize()
+    probe_tflops = 512 * 8 * 20000 * 8 * 32768.0 / (p0.elapsed_time(p1) * 1e-3) / 1e12
 
     for _ in range(args.warmup):
         fwd()
@@ -161,7 +186,10 @@ def main():
                             "logits_avoided_fp32": 4 * N * V},
         "roofline": {"kernel": "fwd_lse_mfma_kernel (timed as cce_forward_ex: + finalize, <1%)",
                      "bound": "mfma", "achieved": fwd_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": fwd_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
+                     "frac": fwd_tflops / MFMA_BF16_PEAK_TFLOPS,
+                     "traffic": MEASURED_FWD_TRAFFIC_BYTES.get(w.spec.name),
+                     "algorithmic_flop_per_launch": fwd_flop,
+                     "mfma_only_loop_tflops_this_box": probe_tflops},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, min(args.cpu_rows, N))

@@ -12,5 +12,5 @@ from .binding import (  # noqa: F401
     CceError, CceOpts, LIB_PATH,
     load, cce_default_opts, cce_workspace_bytes, cce_filter_block, cce_strerror,
     cce_forward, cce_forward_ex, cce_backward, cce_backward_ex, cce_backward_filter_stats,
-    make_opts,
+    make_opts, cce_probe_mfma, cce_probe_copy,
 )

@@ -64,6 +64,10 @@ def load() -> ctypes.CDLL:
         f.restype = ctypes.c_int
     lib.cce_backward_filter_stats.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint64)]
     lib.cce_backward_filter_stats.restype = ctypes.c_int
+    lib.cce_probe_mfma.argtypes = [vp, vp, ctypes.c_int, ctypes.c_int, vp]
+    lib.cce_probe_mfma.restype = ctypes.c_int
+    lib.cce_probe_copy.argtypes = [vp, vp, sz, vp]
+    lib.cce_probe_copy.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -185,3 +189,25 @@ def cce_backward_filter_stats(workspace: Optional[torch.Tensor] = None, stream: 
     st = torch.cuda.current_stream().cuda_stream if stream is None else int(stream)
     _check(load().cce_backward_filter_stats(ws, st, ctypes.byref(total), ctypes.byref(kept)))
     return total.value, kept.value
+
+
+def _hip_check(code: int, what: str) -> None:
+    if code != 0:
+        raise RuntimeError("%s failed with hipError_t %d" % (what, code))
+
+
+def cce_probe_mfma(frags: torch.Tensor, out: torch.Tensor, blocks: int, iters: int, stream: Optional[int] = None) -> None:
+    """Measurement helper (include/cce_probe.h): register-resident MFMA loop."""
+    if frags.numel() * frags.element_size() < 384 * 16 or out.numel() < blocks * 512 or out.dtype != torch.float32:
+        raise ValueError("frags needs 384 * 16 bytes, out blocks * 512 floats")
+    st = torch.cuda.current_stream().cuda_stream if stream is None else int(stream)
+    _hip_check(load().cce_probe_mfma(frags.data_ptr(), out.data_ptr(), int(blocks), int(iters), st), "cce_probe_mfma")
+
+
+def cce_probe_copy(dst: torch.Tensor, src: torch.Tensor, stream: Optional[int] = None) -> None:
+    """Measurement helper (include/cce_probe.h): plain copy of src into dst."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes or nbytes % 16:
+        raise ValueError("dst and src must have the same size, a multiple of 16 bytes")
+    st = torch.cuda.current_stream().cuda_stream if stream is None else int(stream)
+    _hip_check(load().cce_probe_copy(dst.data_ptr(), src.data_ptr(), nbytes, st), "cce_probe_copy")

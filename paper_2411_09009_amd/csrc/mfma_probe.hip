@@ -30,7 +30,28 @@ __global__ __launch_bounds__(512) void mfma_probe_kernel(const bf16x8* __restric
   out[blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
+// Plain 16-byte-per-lane copy: the known-size reference against which the hardware's
+// HBM byte counters are scaled when a profile is read.
+__global__ __launch_bounds__(256) void copy_probe_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n16; i += stride) dst[i] = src[i];
+}
+
 }  // namespace
+
+// Copies `bytes` (a multiple of 16) from src to dst, both device pointers, on `stream`.
+// Returns a hipError_t value.
+extern "C" int cce_probe_copy(void* dst, const void* src, size_t bytes, void* stream) {
+  if (!dst || !src || bytes % 16) return (int)hipErrorInvalidValue;
+  const size_t n16 = bytes / 16;
+  if (n16 == 0) return 0;
+  size_t blocks = (n16 + 255) / 256;
+  if (blocks > 16384) blocks = 16384;
+  hipLaunchKernelGGL(copy_probe_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, (const uint4*)src,
+                     (uint4*)dst, n16);
+  return (int)hipGetLastError();
+}
 
 // Launches `blocks` workgroups of 512 lanes, each wavefront issuing 8 * iters
 // v_mfma_f32_32x32x16_bf16 on fragments taken from `frags` (device, 384 * 16 bytes of

@@ -1,5 +1,5 @@
 """Host-side checks of the C ABI that need no GPU: the library loads, exports every
-symbol include/cce.h declares, sizes its workspaces as documented and rejects bad
+symbol include/*.h declares, sizes its workspaces as documented and rejects bad
 arguments before launching anything."""
 import ctypes
 import os
@@ -13,16 +13,21 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "cce.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(cce_[a-z_]+)\s*\(", text)))
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for h in sorted(os.listdir(inc)):
+        if h.endswith(".h"):
+            text = re.sub(r"/\*.*?\*/", "", open(os.path.join(inc, h)).read(), flags=re.S)
+            names |= set(re.findall(r"\b(cce_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():
     lib = L.load()
     names = declared_symbols()
     assert {"cce_forward", "cce_backward", "cce_forward_ex", "cce_backward_ex", "cce_workspace_bytes",
-            "cce_strerror", "cce_default_opts", "cce_filter_block", "cce_backward_filter_stats"} <= set(names)
+            "cce_strerror", "cce_default_opts", "cce_filter_block", "cce_backward_filter_stats",
+            "cce_probe_mfma", "cce_probe_copy"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
