@@ -49,7 +49,7 @@ constexpr int kMaxKSteps = 2048;   // longest filtered contraction: 131072 / 64
 template <int MODE>
 __global__ __launch_bounds__(kThreads) void bwd_recompute_mfma_kernel(BwdCommon c, BwdMfmaSlab sl, XcdMap map,
                                                                       int tiles_per_split) {
-  __shared__ __attribute__((aligned(1024))) char lds[kLdsBytes];
+  __shared__ __attribute__((aligned(1024))) char lds[kLdsBytes + 8 * 4096];   // operand ring + store staging
   TileCoords tc;
   tc.init();
   int n_tile, split;
@@ -97,6 +97,20 @@ __global__ __launch_bounds__(kThreads) void bwd_recompute_mfma_kernel(BwdCommon 
   const float eps = c.eps;
   const char* P = (const char*)c.C + (int64_t)sl.v0 * ld_bytes;
 
+  // Staging area for the token-major store: 4 KB per wave beyond the operand ring.  A lane
+  // owns one token column of the logit tile, so written straight from registers the
+  // token-major copy would touch 64 different rows per store instruction; through LDS a
+  // store instruction covers 8 rows x 128 contiguous bytes instead.  The 32 x 128 B staging
+  // tile uses the ring's swizzle (16-byte chunk c of row r at position c ^ ((r >> 1) & 7)).
+  // Wave-private, accessed through inline assembly like the ring (see mfma_tile.h); the
+  // LDS executes one wave's accesses in order, so a read sees the writes issued before it.
+  const uint32_t stage_base = lds_addr(lds) + kLdsBytes + (uint32_t)tc.wave * 4096u;
+  const uint32_t st_row = (uint32_t)(tc.lane & 31), st_half = (uint32_t)(tc.lane >> 5);
+  const uint32_t st_wr = stage_base + st_row * 128u + st_half * 8u;       // + ((chunk ^ swz) * 16)
+  const uint32_t st_wswz = (st_row >> 1) & 7u;
+  // read side: instruction rr covers rows rr * 8 + lane / 8, logical chunk lane % 8
+  const uint32_t rd_row = (uint32_t)(tc.lane >> 3), rd_chunk = (uint32_t)(tc.lane & 7);
+
   sweep_tiles(tc, lds, P, c.V - sl.v0, ld_bytes, t0, t1, gQ, offQ, KT, acc, [&](int t) {
     const int vl_base = t * kTileR + tc.wave_r * kWaveRows;   // slab-local vocabulary row of this wave
     bool sig[2] = {false, false};                              // halves rb {0,1} and {2,3}
@@ -109,41 +123,59 @@ __global__ __launch_bounds__(kThreads) void bwd_recompute_mfma_kernel(BwdCommon 
       // Np * vs below 2^30).
       uint32_t nc = (uint32_t)ncol[cb];
       asm volatile("" : "+v"(nc));
-      const uint32_t gz_row = nc * (uint32_t)sl.vs;
 #pragma unroll
-      for (int rb = 0; rb < kRB; ++rb) {
+      for (int rbp = 0; rbp < 2; ++rbp) {
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          bf16 o[4];
-          const int vl = vl_base + rb * 32 + 8 * g + 4 * (tc.lane >> 5);
-          uint32_t gzt_off = (uint32_t)vl * (uint32_t)sl.Np + nc;
+        for (int rbl = 0; rbl < 2; ++rbl) {
+          const int rb = rbp * 2 + rbl;
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const float z = acc[rb][cb][g * 4 + j];
-            acc[rb][cb][g * 4 + j] = 0.f;
-            float a2, dcap;
-            if (MODE == kCap) {
-              float e = __builtin_amdgcn_exp2f(z * cap_scale);
-              float r = __builtin_amdgcn_rcpf(1.f + e);
-              float th = fmaf(-2.f, r, 1.f);           // tanh(z / cap)
-              a2 = cap_l2 * th;
-              dcap = fmaf(-th, th, 1.f);
-            } else {
-              a2 = z * kLog2e;
-              dcap = 1.f;
+          for (int g = 0; g < 4; ++g) {
+            bf16 o[4];
+            const int vl = vl_base + rb * 32 + 8 * g + 4 * (tc.lane >> 5);
+            uint32_t gzt_off = (uint32_t)vl * (uint32_t)sl.Np + nc;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const float z = acc[rb][cb][g * 4 + j];
+              acc[rb][cb][g * 4 + j] = 0.f;
+              float a2, dcap;
+              if (MODE == kCap) {
+                float e = __builtin_amdgcn_exp2f(z * cap_scale);
+                float r = __builtin_amdgcn_rcpf(1.f + e);
+                float th = fmaf(-2.f, r, 1.f);           // tanh(z / cap)
+                a2 = cap_l2 * th;
+                dcap = fmaf(-th, th, 1.f);
+              } else {
+                a2 = z * kLog2e;
+                dcap = 1.f;
+              }
+              const int v = sl.v0 + vl + j;
+              float gval = __builtin_amdgcn_exp2f(a2 - lse2[cb]) - (v == tgt[cb] ? 1.f : 0.f);
+              const bool live = tok && v < c.V;
+              sig[rbp] |= live && fabsf(gval) >= eps;
+              float gz = live ? lam[cb] * gval * dcap : 0.f;
+              o[j] = (bf16)gz;
+              sl.GZT[gzt_off] = o[j];
+              gzt_off += (uint32_t)sl.Np;
             }
-            const int v = sl.v0 + vl + j;
-            float gval = __builtin_amdgcn_exp2f(a2 - lse2[cb]) - (v == tgt[cb] ? 1.f : 0.f);
-            const bool live = tok && v < c.V;
-            sig[rb >> 1] |= live && fabsf(gval) >= eps;
-            float gz = live ? lam[cb] * gval * dcap : 0.f;
-            o[j] = (bf16)gz;
-            sl.GZT[gzt_off] = o[j];
-            gzt_off += (uint32_t)sl.Np;
+            uint2 packed;
+            __builtin_memcpy(&packed, o, 8);
+            // staging row = token (lane & 31), 16-byte chunk = rbl * 4 + g, half = lane >> 5
+            const uint32_t wa = st_wr + ((((uint32_t)(rbl * 4 + g)) ^ st_wswz) << 4);
+            asm volatile("ds_write_b64 %0, %1" ::"v"(wa), "v"(packed));
           }
-          uint2 packed;
-          __builtin_memcpy(&packed, o, 8);
-          *(uint2*)(sl.GZ + (gz_row + (uint32_t)vl)) = packed;
+        }
+        // 32 tokens x 64 vocabulary entries are staged: write them out, 128 contiguous bytes per token
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+          const uint32_t row = (uint32_t)rr * 8u + rd_row;
+          const uint32_t ra = stage_base + row * 128u + ((rd_chunk ^ ((row >> 1) & 7u)) << 4);
+          uint4 val;
+          asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(val) : "v"(ra));
+          // token of this staging row: same wave column block, row-th of the 32 tokens of cb
+          uint32_t tok_row = (uint32_t)(n0 + tc.wave_c * kWaveCols + cb * 32) + row;
+          asm volatile("" : "+v"(tok_row));
+          bf16* dst = sl.GZ + ((size_t)tok_row * (uint32_t)sl.vs + (uint32_t)(vl_base + rbp * 64) + rd_chunk * 8u);
+          *(uint4*)dst = val;
         }
       }
     }

@@ -86,7 +86,7 @@ constexpr int kEventRing = 4;
 struct Helpers {
   std::mutex mutex;
   bool ready = false;
-  hipStream_t product[2] = {};        // [0] dC products, [1] dE products
+  hipStream_t product[3] = {};        // [0], [2] dC products of even / odd slabs, [1] dE products
   hipEvent_t started = nullptr;
   hipEvent_t recomputed[kEventRing] = {};
   hipEvent_t dC_done[kEventRing] = {};
@@ -378,9 +378,12 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
       }
       CCE_HIP(launch_bwd_recompute_mfma(c, s, stream));
       CCE_HIP(hipEventRecord(h->recomputed[e], stream));
-      CCE_HIP(hipStreamWaitEvent(h->product[0], h->recomputed[e], 0));
-      CCE_HIP(launch_bwd_dC_mfma(c, s, out_dC, h->product[0]));
-      CCE_HIP(hipEventRecord(h->dC_done[e], h->product[0]));
+      // dC products of consecutive slabs write disjoint rows: they alternate between two
+      // streams so that the last, partly filled round of one overlaps the next one's start
+      hipStream_t dC_stream = h->product[b ? 2 : 0];
+      CCE_HIP(hipStreamWaitEvent(dC_stream, h->recomputed[e], 0));
+      CCE_HIP(launch_bwd_dC_mfma(c, s, out_dC, dC_stream));
+      CCE_HIP(hipEventRecord(h->dC_done[e], dC_stream));
       // The transposed C slab is needed by the dE product only, so it is made on that
       // product's stream, ahead of the recompute it would otherwise delay (its buffer was
       // last read by the dE product of slab - 2, earlier on the same stream).  dEacc is
@@ -396,6 +399,7 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
     // join: the last record on each helper stream covers everything enqueued on it
     const int e_last = (int)((slab - 1) % kEventRing);
     CCE_HIP(hipStreamWaitEvent(stream, h->dC_done[e_last], 0));
+    if (slab >= 2) CCE_HIP(hipStreamWaitEvent(stream, h->dC_done[(int)((slab - 2) % kEventRing)], 0));
     CCE_HIP(hipStreamWaitEvent(stream, h->dE_done[e_last], 0));
     CCE_HIP(launch_store_dE(dEacc, out_dE, opts->dtype, N * D, stream));
     return CCE_OK;
