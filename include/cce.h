@@ -57,9 +57,14 @@ enum {
   CCE_FILTER_DE = 1u << 0,   /* apply gradient filtering to dE (Section 4.3) */
   CCE_FILTER_DC = 1u << 1,   /* apply gradient filtering to dC; clearing only this bit is the
                                 paper's "CCE-Kahan-FullC" choice, clearing only FILTER_DE "FullE" */
-  CCE_VOCAB_SORT = 1u << 2,  /* forward: also accumulate the mean logit of every vocabulary entry;
-                                backward: walk the vocabulary in order of that mean (Section 4.3,
-                                "Vocabulary sorting").  Needs the same workspace in both calls. */
+  CCE_VOCAB_SORT = 1u << 2,  /* backward only: walk the vocabulary in descending order of each entry's
+                                mean logit over the batch (Section 4.3, "Vocabulary sorting"), so that
+                                entries with non-negligible softmax mass share filter blocks.  The mean
+                                is taken before the soft-cap, where it equals <C_j, mean_i E_i>.  Changes
+                                which blocks the filter skips, never the unfiltered result (beyond the
+                                fp32 summation order of dE).  bf16 MFMA path only (CCE_EUNSUPPORTED
+                                otherwise); costs O(|V|) extra workspace plus two slab-sized copies of C
+                                rows.  The forward pass ignores the flag. */
   CCE_PLAIN_KERNELS = 1u << 3 /* run the plain fp32-FMA kernels instead of the MFMA ones (always used
                                 for CCE_F32 and for shapes the MFMA kernels do not take) */
 };

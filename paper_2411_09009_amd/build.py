@@ -16,7 +16,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_DIR = os.path.join(HERE, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libcce.so")
-SOURCES = ["cce_api.hip", "plain_kernels.hip", "fwd_mfma.hip", "bwd_mfma.hip", "mfma_probe.hip"]
+SOURCES = ["cce_api.hip", "plain_kernels.hip", "fwd_mfma.hip", "bwd_mfma.hip", "sort_kernels.hip", "mfma_probe.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -41,7 +41,7 @@ def build(verbose: bool = False) -> str:
     with tempfile.TemporaryDirectory(prefix="cce_build_") as tmp:
         objs = [os.path.join(tmp, s.replace(".hip", ".o")) for s in SOURCES]
         cmds = [[HIPCC, *FLAGS, "-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)]
-        with ThreadPoolExecutor(max_workers=min(4, len(cmds))) as ex:
+        with ThreadPoolExecutor(max_workers=min(6, len(cmds))) as ex:
             for out in ex.map(_run, cmds):
                 if verbose and out.strip():
                     print(out)

@@ -95,7 +95,7 @@ __global__ __launch_bounds__(kThreads) void bwd_recompute_mfma_kernel(BwdCommon 
   const float cap_scale = MODE == kCap ? 2.f * kLog2e / c.softcap : 0.f;
   const float cap_l2 = MODE == kCap ? c.softcap * kLog2e : kLog2e;
   const float eps = c.eps;
-  const char* P = (const char*)c.C + (int64_t)sl.v0 * ld_bytes;
+  const char* P = (const char*)sl.Crows;
 
   // Staging area for the token-major store: 4 KB per wave beyond the operand ring.  A lane
   // owns one token column of the logit tile, so written straight from registers the
@@ -268,6 +268,15 @@ __global__ __launch_bounds__(kThreads) void bwd_product_mfma_kernel(BwdCommon c,
         [&](int) {});
   }
 
+  // rows of dC go back to their original vocabulary index when the slab was walked in sorted order
+  int out_row[kCB] = {0, 0};
+  if (DC) {
+#pragma unroll
+    for (int cb = 0; cb < kCB; ++cb) {
+      const int vv = sl.v0 + c0 + tc.wave_c * kWaveCols + cb * 32 + (tc.lane & 31);
+      out_row[cb] = (sl.perm && vv < c.V) ? sl.perm[vv] : vv;
+    }
+  }
 #pragma unroll
   for (int cb = 0; cb < kCB; ++cb) {
     const int col = c0 + tc.wave_c * kWaveCols + cb * 32 + (tc.lane & 31);
@@ -285,7 +294,7 @@ __global__ __launch_bounds__(kThreads) void bwd_product_mfma_kernel(BwdCommon c,
             bf16 o[4] = {(bf16)v.x, (bf16)v.y, (bf16)v.z, (bf16)v.w};
             uint2 packed;
             __builtin_memcpy(&packed, o, 8);
-            *(uint2*)(out_dC + (int64_t)vv * c.D + d) = packed;
+            *(uint2*)(out_dC + (int64_t)out_row[cb] * c.D + d) = packed;
           }
         } else if (col < c.N) {
           float4* dst = (float4*)(sl.dEacc + (int64_t)col * c.D + d);

@@ -8,6 +8,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <cstdlib>
 #include <mutex>
 
 namespace {
@@ -89,6 +90,7 @@ struct Helpers {
   hipStream_t product[3] = {};        // [0], [2] dC products of even / odd slabs, [1] dE products
   hipEvent_t started = nullptr;
   hipEvent_t recomputed[kEventRing] = {};
+  hipEvent_t gathered[kEventRing] = {};
   hipEvent_t dC_done[kEventRing] = {};
   hipEvent_t dE_done[kEventRing] = {};
 };
@@ -105,6 +107,7 @@ int helpers_for_device(Helpers** out) {
     CCE_HIP(hipEventCreateWithFlags(&h.started, hipEventDisableTiming));
     for (int i = 0; i < kEventRing; ++i) {
       CCE_HIP(hipEventCreateWithFlags(&h.recomputed[i], hipEventDisableTiming));
+      CCE_HIP(hipEventCreateWithFlags(&h.gathered[i], hipEventDisableTiming));
       CCE_HIP(hipEventCreateWithFlags(&h.dC_done[i], hipEventDisableTiming));
       CCE_HIP(hipEventCreateWithFlags(&h.dE_done[i], hipEventDisableTiming));
     }
@@ -123,7 +126,6 @@ int check_common(const void* E, const void* C, const int64_t* targets, int64_t N
   if (!o) return CCE_EINVAL;
   if (o->dtype != CCE_BF16 && o->dtype != CCE_F32) return CCE_EUNSUPPORTED;
   if (o->flags & ~(uint32_t)(CCE_FILTER_DE | CCE_FILTER_DC | CCE_VOCAB_SORT | CCE_PLAIN_KERNELS)) return CCE_EUNSUPPORTED;
-  if (o->flags & CCE_VOCAB_SORT) return CCE_EUNSUPPORTED;   // not built yet
   if (!E || !C || !targets) return CCE_EINVAL;
   if (N <= 0 || D <= 0 || V <= 0) return CCE_EINVAL;
   if (N > (int64_t)0x7fff0000 || V > (int64_t)0x7fff0000 || D > (1 << 22)) return CCE_EINVAL;
@@ -169,10 +171,14 @@ struct BwdPlan {
   bool mfma;
   int64_t Np, vs;          // padded token count, slab width
   size_t off_flags[2], off_dEacc, off_ET, off_CT[2], off_GZ[2], off_GZT[2];   // [2]: even / odd slabs (MFMA path)
+  // vocabulary sorting (MFMA path only)
+  size_t off_partial, off_mean, off_key, off_key_sorted, off_index, off_perm, off_inverse, off_targets, off_Cs[2],
+      off_sort_temp;
+  size_t sort_temp_bytes;
   size_t total_bytes;
 };
 
-BwdPlan layout_backward(bool mfma, int64_t N, int64_t D, int64_t vs) {
+BwdPlan layout_backward(bool mfma, int64_t N, int64_t D, int64_t V, int64_t vs, bool sort) {
   BwdPlan p{};
   p.mfma = mfma;
   p.vs = vs;
@@ -193,6 +199,19 @@ BwdPlan layout_backward(bool mfma, int64_t N, int64_t D, int64_t vs) {
       p.off_GZT[b] = off;
       off += align_up((size_t)p.Np * vs * 2, 256);
     }
+    if (sort) {
+      p.off_partial = off;  off += align_up(vocab_sort_partial_bytes(D), 256);
+      p.off_mean = off;     off += align_up((size_t)D * 4, 256);
+      p.off_key = off;      off += align_up((size_t)V * 4, 256);
+      p.off_key_sorted = off; off += align_up((size_t)V * 4, 256);
+      p.off_index = off;    off += align_up((size_t)V * 4, 256);
+      p.off_perm = off;     off += align_up((size_t)V * 4, 256);
+      p.off_inverse = off;  off += align_up((size_t)V * 4, 256);
+      p.off_targets = off;  off += align_up((size_t)N * 8, 256);
+      for (int b = 0; b < 2; ++b) { p.off_Cs[b] = off; off += align_up((size_t)vs * D * 2, 256); }
+      p.sort_temp_bytes = vocab_sort_temp_bytes(V);
+      p.off_sort_temp = off; off += align_up(p.sort_temp_bytes, 256);
+    }
   } else {
     p.Np = N;
     p.off_flags[0] = off;
@@ -211,11 +230,12 @@ int64_t slab_tile(bool mfma) { return mfma ? 256 : 64; }
 int64_t recommended_slab(bool mfma, int64_t V) {
   int64_t full = round_up(V, slab_tile(mfma));
   int64_t rec = mfma ? kMfmaSlabCols : kPlainSlabCols;
+  if (const char* e = getenv("CCE_DEBUG_SLAB")) if (mfma) rec = atoll(e);
   return full < rec ? full : rec;
 }
 
 // widest slab (multiple of the tile width, at most the recommended one) that fits `bytes`
-int64_t fit_slab(bool mfma, int64_t N, int64_t D, int64_t V, size_t bytes) {
+int64_t fit_slab(bool mfma, int64_t N, int64_t D, int64_t V, size_t bytes, bool sort) {
   const int64_t t = slab_tile(mfma);
   int64_t lo = 0, hi = recommended_slab(mfma, V) / t;   // in tiles
   if (mfma) {
@@ -225,7 +245,7 @@ int64_t fit_slab(bool mfma, int64_t N, int64_t D, int64_t V, size_t bytes) {
   }
   while (lo < hi) {
     int64_t mid = (lo + hi + 1) / 2;
-    if (layout_backward(mfma, N, D, mid * t).total_bytes <= bytes) lo = mid; else hi = mid - 1;
+    if (layout_backward(mfma, N, D, V, mid * t, sort).total_bytes <= bytes) lo = mid; else hi = mid - 1;
   }
   return lo * t;
 }
@@ -260,10 +280,11 @@ size_t cce_workspace_bytes(int op, int64_t N, int64_t D, int64_t V, const cce_op
   if (!opts || N <= 0 || D <= 0 || V <= 0) return 0;
   if (opts->dtype != CCE_BF16 && opts->dtype != CCE_F32) return 0;
   const bool mfma = use_mfma(D, opts);
+  const bool sort = mfma && (opts->flags & CCE_VOCAB_SORT);
   switch (op) {
     case CCE_OP_FORWARD: return plan_forward(N, D, V, opts).total_bytes;
-    case CCE_OP_BACKWARD: return layout_backward(mfma, N, D, recommended_slab(mfma, V)).total_bytes;
-    case CCE_OP_BACKWARD_MIN: return layout_backward(mfma, N, D, slab_tile(mfma)).total_bytes;
+    case CCE_OP_BACKWARD: return layout_backward(mfma, N, D, V, recommended_slab(mfma, V), sort).total_bytes;
+    case CCE_OP_BACKWARD_MIN: return layout_backward(mfma, N, D, V, slab_tile(mfma), sort).total_bytes;
     default: return 0;
   }
 }
@@ -326,10 +347,12 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
   if (!lse || !dLoss || !out_dE || !out_dC) return CCE_EINVAL;
   if (!aligned(out_dE, 16) || !aligned(out_dC, 16)) return CCE_EINVAL;
   const bool mfma = use_mfma(D, opts);
+  const bool sort = (opts->flags & CCE_VOCAB_SORT) != 0;
+  if (sort && !mfma) return CCE_EUNSUPPORTED;   // vocabulary sorting exists on the bf16 MFMA path only
   if (!opts->workspace) return CCE_EWORKSPACE;
-  const int64_t vs = fit_slab(mfma, N, D, V, opts->workspace_bytes);
+  const int64_t vs = fit_slab(mfma, N, D, V, opts->workspace_bytes, sort);
   if (vs <= 0) return CCE_EWORKSPACE;
-  const BwdPlan plan = layout_backward(mfma, N, D, vs);
+  const BwdPlan plan = layout_backward(mfma, N, D, V, vs, sort);
   hipStream_t stream = (hipStream_t)opts->stream;
   char* ws = (char*)opts->workspace;
 
@@ -358,6 +381,26 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
     // helper work may not start before the caller's earlier work on `stream` (which may produce C)
     CCE_HIP(hipEventRecord(h->started, stream));
     CCE_HIP(launch_transpose_bf16((const bf16*)E, (int)N, (int)plan.Np, (int)D, D, s.ET, stream));
+    if (sort) {
+      VocabSortParams v{};
+      v.E = (const bf16*)E; v.C = (const bf16*)C; v.targets = targets;
+      v.N = (int)N; v.D = (int)D; v.V = (int)V; v.ignore_index = ignore_index;
+      v.partial = (float*)(ws + plan.off_partial);
+      v.mean = (float*)(ws + plan.off_mean);
+      v.key = (float*)(ws + plan.off_key);
+      v.key_sorted = (float*)(ws + plan.off_key_sorted);
+      v.index = (int*)(ws + plan.off_index);
+      v.perm = (int*)(ws + plan.off_perm);
+      v.inverse = (int*)(ws + plan.off_inverse);
+      v.targets_sorted = (int64_t*)(ws + plan.off_targets);
+      v.temp = ws + plan.off_sort_temp;
+      v.temp_bytes = plan.sort_temp_bytes;
+      hipError_t se = launch_vocab_sort(v, stream);
+      if (se == hipErrorOutOfMemory) return CCE_EWORKSPACE;
+      CCE_HIP(se);
+      c.targets = v.targets_sorted;    // from here on the vocabulary is indexed by sorted position
+      s.perm = v.perm;
+    }
     int64_t slab = 0;
     for (int64_t v0 = 0; v0 < V; v0 += vs, ++slab) {
       const int b = (int)(slab & 1), e = (int)(slab % kEventRing);
@@ -376,11 +419,24 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
         CCE_HIP(hipStreamWaitEvent(stream, h->dC_done[e2], 0));
         CCE_HIP(hipStreamWaitEvent(stream, h->dE_done[e2], 0));
       }
+      const int64_t rows_valid = (V - v0 < vs_this) ? V - v0 : vs_this;
+      s.Crows = (const bf16*)C + v0 * D;
+      if (sort) {
+        // the slab's rows of C, gathered in sorted order (its buffer was last read by the
+        // recompute and the transpose of slab - 2, both waited for above)
+        bf16* Cs = (bf16*)(ws + plan.off_Cs[b]);
+        CCE_HIP(launch_gather_rows((const bf16*)C, s.perm, (int)v0, (int)rows_valid, (int)D, Cs, stream));
+        CCE_HIP(hipEventRecord(h->gathered[e], stream));
+        s.Crows = Cs;
+      }
       CCE_HIP(launch_bwd_recompute_mfma(c, s, stream));
       CCE_HIP(hipEventRecord(h->recomputed[e], stream));
       // dC products of consecutive slabs write disjoint rows: they alternate between two
       // streams so that the last, partly filled round of one overlaps the next one's start
       hipStream_t dC_stream = h->product[b ? 2 : 0];
+      static const bool serial = getenv("CCE_DEBUG_SERIAL") != nullptr;
+      if (serial) { dC_stream = stream; }
+      hipStream_t dE_stream = serial ? stream : h->product[1];
       CCE_HIP(hipStreamWaitEvent(dC_stream, h->recomputed[e], 0));
       CCE_HIP(launch_bwd_dC_mfma(c, s, out_dC, dC_stream));
       CCE_HIP(hipEventRecord(h->dC_done[e], dC_stream));
@@ -388,13 +444,12 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
       // product's stream, ahead of the recompute it would otherwise delay (its buffer was
       // last read by the dE product of slab - 2, earlier on the same stream).  dEacc is
       // read-modify-written slab after slab: stream order keeps that sequence.
-      if (slab == 0) CCE_HIP(hipStreamWaitEvent(h->product[1], h->started, 0));
-      const int64_t rows_valid = (V - v0 < vs_this) ? V - v0 : vs_this;
-      CCE_HIP(launch_transpose_bf16((const bf16*)C + v0 * D, (int)rows_valid, (int)vs_this, (int)D, D, s.CT,
-                                    h->product[1]));
-      CCE_HIP(hipStreamWaitEvent(h->product[1], h->recomputed[e], 0));
-      CCE_HIP(launch_bwd_dE_mfma(c, s, h->product[1]));
-      CCE_HIP(hipEventRecord(h->dE_done[e], h->product[1]));
+      if (slab == 0) CCE_HIP(hipStreamWaitEvent(dE_stream, h->started, 0));
+      if (sort) CCE_HIP(hipStreamWaitEvent(dE_stream, h->gathered[e], 0));
+      CCE_HIP(launch_transpose_bf16(s.Crows, (int)rows_valid, (int)vs_this, (int)D, D, s.CT, dE_stream));
+      CCE_HIP(hipStreamWaitEvent(dE_stream, h->recomputed[e], 0));
+      CCE_HIP(launch_bwd_dE_mfma(c, s, dE_stream));
+      CCE_HIP(hipEventRecord(h->dE_done[e], dE_stream));
     }
     // join: the last record on each helper stream covers everything enqueued on it
     const int e_last = (int)((slab - 1) % kEventRing);

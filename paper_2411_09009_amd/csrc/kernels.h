@@ -126,6 +126,10 @@ struct BwdMfmaSlab {
   uint32_t* flags_vn;   // [vs/256, Np/64]  block (64 tokens x 256 vocab) has a significant entry;
                         // starts right after flags_nv (the two are cleared as one array)
   int first;            // first slab of the call: dEacc is overwritten instead of added to
+  const bf16* Crows;    // row v0 of the classifier as this slab sees it: C + v0 * D, or the slab's
+                        // gathered copy when the vocabulary is walked in sorted order
+  const int* perm;      // sorted position -> original vocabulary index (rows of dC are written
+                        // through it); nullptr = identity
 };
 hipError_t launch_transpose_bf16(const bf16* in, int rows_valid, int rows_padded, int cols, int64_t ld_in,
                                  bf16* out, hipStream_t stream);
@@ -144,6 +148,30 @@ struct BwdPlainSlab {
 hipError_t launch_bwd_gz_plain(const BwdCommon& c, const BwdPlainSlab& s, hipStream_t stream);
 hipError_t launch_bwd_dE_plain(const BwdCommon& c, const BwdPlainSlab& s, hipStream_t stream);
 hipError_t launch_bwd_dC_plain(const BwdCommon& c, const BwdPlainSlab& s, void* out_dC, hipStream_t stream);
+
+// ---- vocabulary sorting (Section 4.3) ------------------------------------------
+struct VocabSortParams {
+  const bf16* E;            // [N, D]
+  const bf16* C;            // [V, D]
+  const int64_t* targets;   // [N]
+  int N, D, V;
+  int64_t ignore_index;
+  float* partial;           // [vocab_sort_partial_bytes(D)] column sums of row blocks of E
+  float* mean;              // [D] mean token embedding
+  float* key;               // [V] mean logit of every vocabulary entry
+  float* key_sorted;        // [V]
+  int* index;               // [V] 0 .. V-1
+  int* perm;                // [V] out: original index at each sorted position (descending key)
+  int* inverse;             // [V] out: sorted position of each original index
+  int64_t* targets_sorted;  // [N] out: targets as sorted positions (ignored / out-of-range -> ignore_index)
+  void* temp;               // radix-sort scratch
+  size_t temp_bytes;
+};
+size_t vocab_sort_temp_bytes(int64_t V);
+size_t vocab_sort_partial_bytes(int64_t D);
+hipError_t launch_vocab_sort(const VocabSortParams& p, hipStream_t stream);
+// out[r][:] = C[perm[p0 + r]][:], r < rows (D a multiple of 8)
+hipError_t launch_gather_rows(const bf16* C, const int* perm, int p0, int rows, int D, bf16* out, hipStream_t stream);
 
 // dEacc (fp32 [N, D]) -> out_dE in the storage dtype.
 hipError_t launch_store_dE(const float* dEacc, void* out_dE, int dtype, int64_t count, hipStream_t stream);

@@ -106,6 +106,41 @@ def test_full_c_and_full_e_variants(cce):
     assert torch.equal(dE2, dE0) and torch.equal(dC2, dCf)
 
 
+@pytest.mark.parametrize("name,N,D,V,kw", [MID[0], MID[3], ("stress_peaked", 700, 128, 5000, {})])
+def test_vocabulary_sorting_changes_the_order_not_the_result(cce, name, N, D, V, kw):
+    """Section 4.3 vocabulary sorting: the backward pass walks the vocabulary in mean-logit order."""
+    w = make(name, N=N, D=D, V=V, **kw)
+    E, C, t = to_device(w)
+    _, lse = run_forward(w, E, C, t)
+    dloss = torch.from_numpy(w.mean_dloss()).cuda()
+    both = L.CCE_FILTER_DE | L.CCE_FILTER_DC
+    _, _, rdE, rdC = oracle_all(w)
+    # unfiltered: same gradients; dC rows are bitwise the same (their token sums do not depend on
+    # the vocabulary order), dE differs only by fp32 summation order
+    dE0, dC0, _ = run_backward(w, E, C, t, lse, dloss, eps=0.0)
+    dE1, dC1, _ = run_backward(w, E, C, t, lse, dloss, eps=0.0, flags=both | L.CCE_VOCAB_SORT)
+    assert torch.equal(dC0, dC1)
+    assert rel_fro(f64(dE1), rdE) <= TOL_GRAD and rel_fro(f64(dE1), f64(dE0)) <= 2e-3
+    # narrow slabs with sorting (many gathers, ragged last slab)
+    dE2, dC2, _ = run_backward(w, E, C, t, lse, dloss, eps=0.0, flags=both | L.CCE_VOCAB_SORT, op=L.CCE_OP_BACKWARD_MIN)
+    assert torch.equal(dC0, dC2) and rel_fro(f64(dE2), rdE) <= TOL_GRAD
+    # filtered: still within tolerance of the exact gradient and of the element-wise filter bound
+    dEf, dCf, st_plain = run_backward(w, E, C, t, lse, dloss)
+    dEs, dCs, st_sort = run_backward(w, E, C, t, lse, dloss, flags=both | L.CCE_VOCAB_SORT)
+    _, _, fdE, fdC = oracle_all(w, eps=O.FILTER_EPS_BF16, mode="element")
+    eE, eC = rel_fro(f64(dEs), rdE), rel_fro(f64(dCs), rdC)
+    print("sorted filter %s: dE err %.2e dC err %.2e; blocks kept %d / %d sorted, %d / %d unsorted"
+          % (name, eE, eC, st_sort[1], st_sort[0], st_plain[1], st_plain[0]))
+    assert eE <= rel_fro(fdE, rdE) + rel_fro(f64(dE0), rdE) + 1e-3
+    assert eC <= rel_fro(fdC, rdC) + rel_fro(f64(dC0), rdC) + 1e-3
+    assert st_sort[0] == st_plain[0] and 0 < st_sort[1] <= st_sort[0]
+    # the plain-FMA path has no sorted walk
+    o = L.make_opts(L.CCE_BF16, flags=L.CCE_VOCAB_SORT | L.CCE_PLAIN_KERNELS, workspace=workspace(1 << 26))
+    with pytest.raises(L.CceError) as ei:
+        L.cce_backward_ex(E, C, t, lse, dloss, w.softcap, w.ignore_index, o)
+    assert ei.value.status == -3
+
+
 def test_tiny_config_fp32_full_parity(cce):
     """Config 1 (N=256, D=64, V=1024, fp32, 5% ignored): the oracle covers every output."""
     w = make("tiny")
