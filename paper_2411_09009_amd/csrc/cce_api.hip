@@ -35,6 +35,7 @@ constexpr int kMaxDevices = 64;
 constexpr int64_t kMfmaSlabCols = 8192;  // recommended backward slab width (vocabulary entries), MFMA path
 constexpr int64_t kPlainSlabCols = 4096;
 constexpr int kMaxFilteredKSteps = 2048;
+constexpr int kSlabBuffers = 2;          // vocabulary slabs in flight in the MFMA backward pass
 
 int cu_count() {
   static int cached[kMaxDevices] = {};
@@ -170,9 +171,9 @@ FwdPlan plan_forward(int64_t N, int64_t D, int64_t V, const cce_opts* o) {
 struct BwdPlan {
   bool mfma;
   int64_t Np, vs;          // padded token count, slab width
-  size_t off_flags[2], off_dEacc, off_ET, off_CT[2], off_GZ[2], off_GZT[2];   // [2]: even / odd slabs (MFMA path)
+  size_t off_flags[kSlabBuffers], off_dEacc, off_ET, off_CT[kSlabBuffers], off_GZ[kSlabBuffers], off_GZT[kSlabBuffers];   // one set per slab in flight (MFMA path)
   // vocabulary sorting (MFMA path only)
-  size_t off_partial, off_mean, off_key, off_key_sorted, off_index, off_perm, off_inverse, off_targets, off_Cs[2],
+  size_t off_partial, off_mean, off_key, off_key_sorted, off_index, off_perm, off_inverse, off_targets, off_Cs[kSlabBuffers],
       off_sort_temp;
   size_t sort_temp_bytes;
   size_t total_bytes;
@@ -189,7 +190,7 @@ BwdPlan layout_backward(bool mfma, int64_t N, int64_t D, int64_t V, int64_t vs, 
     off += align_up((size_t)N * D * 4, 256);
     p.off_ET = off;
     off += align_up((size_t)D * p.Np * 2, 256);
-    for (int b = 0; b < 2; ++b) {
+    for (int b = 0; b < kSlabBuffers; ++b) {
       p.off_flags[b] = off;
       off += align_up(((size_t)(p.Np / 256) * (vs / 64) + (size_t)(vs / 256) * (p.Np / 64)) * 4, 256);
       p.off_CT[b] = off;
@@ -208,7 +209,7 @@ BwdPlan layout_backward(bool mfma, int64_t N, int64_t D, int64_t V, int64_t vs, 
       p.off_perm = off;     off += align_up((size_t)V * 4, 256);
       p.off_inverse = off;  off += align_up((size_t)V * 4, 256);
       p.off_targets = off;  off += align_up((size_t)N * 8, 256);
-      for (int b = 0; b < 2; ++b) { p.off_Cs[b] = off; off += align_up((size_t)vs * D * 2, 256); }
+      for (int b = 0; b < kSlabBuffers; ++b) { p.off_Cs[b] = off; off += align_up((size_t)vs * D * 2, 256); }
       p.sort_temp_bytes = vocab_sort_temp_bytes(V);
       p.off_sort_temp = off; off += align_up(p.sort_temp_bytes, 256);
     }
@@ -403,7 +404,7 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
     }
     int64_t slab = 0;
     for (int64_t v0 = 0; v0 < V; v0 += vs, ++slab) {
-      const int b = (int)(slab & 1), e = (int)(slab % kEventRing);
+      const int b = (int)(slab % kSlabBuffers), e = (int)(slab % kEventRing);
       const int64_t vs_this = (round_up(V - v0, 256) < vs) ? round_up(V - v0, 256) : vs;
       s.v0 = (int)v0;
       s.vs = (int)vs_this;
@@ -413,9 +414,9 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
       s.GZT = (bf16*)(ws + plan.off_GZT[b]);
       s.flags_nv = (uint32_t*)(ws + plan.off_flags[b]);
       s.flags_vn = s.flags_nv + (plan.Np / 256) * (vs_this / 64);
-      if (slab >= 2) {
-        // this slab's buffers were last read by the products of slab - 2
-        const int e2 = (int)((slab - 2) % kEventRing);
+      if (slab >= kSlabBuffers) {
+        // this slab's buffers were last read by the products of slab - kSlabBuffers
+        const int e2 = (int)((slab - kSlabBuffers) % kEventRing);
         CCE_HIP(hipStreamWaitEvent(stream, h->dC_done[e2], 0));
         CCE_HIP(hipStreamWaitEvent(stream, h->dE_done[e2], 0));
       }
@@ -433,7 +434,7 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
       CCE_HIP(hipEventRecord(h->recomputed[e], stream));
       // dC products of consecutive slabs write disjoint rows: they alternate between two
       // streams so that the last, partly filled round of one overlaps the next one's start
-      hipStream_t dC_stream = h->product[b ? 2 : 0];
+      hipStream_t dC_stream = h->product[(slab & 1) ? 2 : 0];
       static const bool serial = getenv("CCE_DEBUG_SERIAL") != nullptr;
       if (serial) { dC_stream = stream; }
       hipStream_t dE_stream = serial ? stream : h->product[1];

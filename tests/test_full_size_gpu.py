@@ -90,3 +90,12 @@ def test_full_size_matches_stored_oracle(cce, name):
           % (fE, elemE, fC, elemC, stats_f[1], stats_f[0]), flush=True)
     assert fE <= elemE + eE + 1e-3 and fC <= elemC + eC + 1e-3
     assert 0 < stats_f[1] <= stats_f[0]
+
+    print("backward (filtered, vocabulary sorted) %s" % name, flush=True)
+    flags = L.CCE_FILTER_DE | L.CCE_FILTER_DC | L.CCE_VOCAB_SORT
+    dEs, dCs, stats_s = run_backward(w, E, C, t, lse, dloss, flags=flags)
+    sE, sC = rel_fro(rows_of(dEs, er), ref_dE), rel_fro(rows_of(dCs, vr), ref_dC)
+    print("  sorted:   dE rows err %.2e  dC rows err %.2e  blocks kept %d / %d" % (sE, sC, stats_s[1], stats_s[0]),
+          flush=True)
+    assert sE <= elemE + eE + 1e-3 and sC <= elemC + eC + 1e-3
+    assert stats_s[0] == stats_f[0] and 0 < stats_s[1] <= stats_s[0]
