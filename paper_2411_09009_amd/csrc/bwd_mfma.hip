@@ -7,40 +7,21 @@
 // the two fp32 output tiles, so the pass is restructured around vocabulary
 // slabs; within a slab
 //   1. recompute kernel: logit tiles as in the forward pass, then
-//      gz = dloss * (exp(a - lse) - onehot) * a'  written once as bf16, both
-//      token-major (GZ) and vocabulary-major (GZT), plus block flags for the
-//      gradient filter;
-//   2. dC[slab] = GZT * E^T-slice product, final after one pass over the tokens;
-//   3. dE += GZ * C^T-slab product, accumulated in fp32 across slabs by plain
-//      (exclusive-owner) read-modify-write.
-// All three are the same NT MFMA contraction (mfma_tile.h); the operands that
-// are not K-contiguous in the caller's layout (E and the C slab, contracted over
-// tokens / vocabulary) are transposed once into the workspace.
+//      gz = dloss * (exp(a - lse) - onehot) * a'  written once as bf16,
+//      token-major (GZ [Np, vs]), plus block flags for the gradient filter;
+//   2. dC[slab] = GZ^T E product (contraction over tokens), final after one pass;
+//   3. dE += GZ C[slab] product (contraction over the slab), accumulated in fp32
+//      across slabs by plain (exclusive-owner) read-modify-write.
+// All three run on the same MFMA tile engine (mfma_tile.h).  Operands whose
+// contracted index is not contiguous in memory (E and GZ over tokens, the rows of C
+// over the vocabulary) are read in place as "K-major" operands through the LDS
+// transposing reads; nothing is transposed in memory.
 #include "kernels.h"
 #include "mfma_tile.h"
 
 namespace cce {
 
 namespace {
-
-// ------------------------------------------------------------------ transpose
-// out[c][r] = r < rows_valid ? in[r][c] : 0     (out is [cols][rows_padded])
-__global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t* __restrict__ in, int rows_valid,
-                                                             int rows_padded, int cols, int64_t ld_in,
-                                                             uint16_t* __restrict__ out) {
-  __shared__ uint16_t tile[64][66];
-  const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  for (int j = ty; j < 64; j += 4) {
-    int r = r0 + j, c = c0 + tx;
-    tile[j][tx] = (r < rows_valid && c < cols) ? in[(int64_t)r * ld_in + c] : (uint16_t)0;
-  }
-  __syncthreads();
-  for (int j = ty; j < 64; j += 4) {
-    int c = c0 + j, r = r0 + tx;
-    if (c < cols && r < rows_padded) out[(int64_t)c * rows_padded + r] = tile[tx][j];
-  }
-}
 
 enum { kNoCap = 0, kCap = 1 };
 constexpr int kMaxKSteps = 2048;   // longest filtered contraction: 131072 / 64
@@ -117,12 +98,6 @@ __global__ __launch_bounds__(kThreads) void bwd_recompute_mfma_kernel(BwdCommon 
 #pragma unroll
     for (int cb = 0; cb < kCB; ++cb) {
       const bool tok = tgt[cb] >= 0;
-      // Keep the store-address arithmetic inside the epilogue: derived from an opaque copy of
-      // the column index, it cannot be hoisted out of the tile loop and held in registers
-      // across the MFMA stages.  Offsets are 32-bit element indices (the dispatcher keeps
-      // Np * vs below 2^30).
-      uint32_t nc = (uint32_t)ncol[cb];
-      asm volatile("" : "+v"(nc));
 #pragma unroll
       for (int rbp = 0; rbp < 2; ++rbp) {
 #pragma unroll
@@ -132,7 +107,6 @@ __global__ __launch_bounds__(kThreads) void bwd_recompute_mfma_kernel(BwdCommon 
           for (int g = 0; g < 4; ++g) {
             bf16 o[4];
             const int vl = vl_base + rb * 32 + 8 * g + 4 * (tc.lane >> 5);
-            uint32_t gzt_off = (uint32_t)vl * (uint32_t)sl.Np + nc;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
               const float z = acc[rb][cb][g * 4 + j];
@@ -154,8 +128,6 @@ __global__ __launch_bounds__(kThreads) void bwd_recompute_mfma_kernel(BwdCommon 
               sig[rbp] |= live && fabsf(gval) >= eps;
               float gz = live ? lam[cb] * gval * dcap : 0.f;
               o[j] = (bf16)gz;
-              sl.GZT[gzt_off] = o[j];
-              gzt_off += (uint32_t)sl.Np;
             }
             uint2 packed;
             __builtin_memcpy(&packed, o, 8);
@@ -171,7 +143,9 @@ __global__ __launch_bounds__(kThreads) void bwd_recompute_mfma_kernel(BwdCommon 
           const uint32_t ra = stage_base + row * 128u + ((rd_chunk ^ ((row >> 1) & 7u)) << 4);
           uint4 val;
           asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(val) : "v"(ra));
-          // token of this staging row: same wave column block, row-th of the 32 tokens of cb
+          // token of this staging row: same wave column block, row-th of the 32 tokens of cb.
+          // The address is derived from an opaque copy so that it is computed here and not
+          // hoisted out of the tile loop into registers that stay live across the MFMA stages.
           uint32_t tok_row = (uint32_t)(n0 + tc.wave_c * kWaveCols + cb * 32) + row;
           asm volatile("" : "+v"(tok_row));
           bf16* dst = sl.GZ + ((size_t)tok_row * (uint32_t)sl.vs + (uint32_t)(vl_base + rbp * 64) + rd_chunk * 8u);
@@ -195,8 +169,8 @@ __global__ __launch_bounds__(kThreads) void bwd_recompute_mfma_kernel(BwdCommon 
 // ------------------------------------------------------------------ gradient products
 // out tile [256 d x 256 c]:  acc[d][c] = sum_k P[d][k] * Q[c][k],  k stepping over 64-wide
 // blocks; with FILTERED only the blocks whose flag (row tile_c of `flags`) is set.
-//   DC = false:  P = CT [D, vs], Q = GZ  [Np, vs], c = token      -> dEacc[c][d] (+)= acc
-//   DC = true :  P = ET [D, Np], Q = GZT [vs, Np], c = vocabulary -> dC[v0 + c][d] = bf16(acc)
+//   DC = false:  P = C slab [vs, D] (K-major), Q = GZ [Np, vs] rows,      c = token      -> dEacc[c][d] (+)= acc
+//   DC = true :  P = E [N, D] (K-major),       Q = GZ [Np, vs] (K-major), c = vocabulary -> dC[v0 + c][d] = bf16(acc)
 template <bool DC, bool FILTERED>
 __global__ __launch_bounds__(kThreads) void bwd_product_mfma_kernel(BwdCommon c, BwdMfmaSlab sl, bf16* out_dC,
                                                                     XcdMap map) {
@@ -209,9 +183,14 @@ __global__ __launch_bounds__(kThreads) void bwd_product_mfma_kernel(BwdCommon c,
   if (!xcd_map_decode(map, blockIdx.x, tile_r, tile_c)) return;
   const int d0 = tile_r * kTileR, c0 = tile_c * kTileC;
   const int K = DC ? sl.Np : sl.vs;
-  const int64_t ld_bytes = (int64_t)K * 2;
-  const char* P = (const char*)(DC ? sl.ET : sl.CT) + (int64_t)d0 * ld_bytes;
-  const char* Q = (const char*)(DC ? sl.GZT : sl.GZ) + (int64_t)c0 * ld_bytes;
+  // P is always K-major: E [N, D] contracted over tokens (dC) or the slab's rows of C [vs, D]
+  // contracted over the vocabulary (dE); its tile is columns d0 .. d0 + 255 of every K-row.
+  // Q is GZ [Np, vs]: K-major for dC (columns = vocabulary tile), K-contiguous for dE (rows = token tile).
+  const uint32_t ldP = (uint32_t)c.D * 2u, ldQ = (uint32_t)sl.vs * 2u;
+  const char* P = (const char*)(DC ? c.E : (const void*)sl.Crows) + (int64_t)d0 * 2;
+  const int kP_last = DC ? c.N - 1 : min(sl.vs, c.V - sl.v0) - 1;   // K-rows past the operand's end repeat the last one
+                                                                     // (the matching GZ entries are zero)
+  const char* Q = (const char*)sl.GZ + (DC ? (int64_t)c0 * 2 : (int64_t)c0 * ldQ);
   const int ksteps = K / kTileK;
 
   int kcount = ksteps;
@@ -242,12 +221,14 @@ __global__ __launch_bounds__(kThreads) void bwd_product_mfma_kernel(BwdCommon c,
       for (int i = 0; i < 16; ++i) acc[rb][cb][i] = 0.f;
 
   if (kcount > 0) {
-    uint32_t offP[4], offQ[4];
-    dma_offsets(tc, min(kTileR, c.D - d0), ld_bytes, offP);
-    dma_offsets(tc, kTileC, ld_bytes, offQ);     // Q rows are padded to full tiles in the workspace
+    KMajorLane laneP, laneQ;
+    laneP.init(tc, min(32, (c.D - d0) / 8));
+    uint32_t offQ[4];
+    if (DC) laneQ.init(tc, 32);
+    else dma_offsets(tc, kTileC, ldQ, offQ);     // GZ rows are padded to full tiles in the workspace
     const uint32_t klist_addr = lds_addr(klist);
     int cursor = 0;
-    mma_pipeline(
+    mma_pipeline<true, DC>(
         tc, lds, kcount, acc,
         [&](StageSrc& src) {
           int kstep = cursor;
@@ -259,11 +240,16 @@ __global__ __launch_bounds__(kThreads) void bwd_product_mfma_kernel(BwdCommon c,
             kstep = __builtin_amdgcn_readfirstlane((int)v);
           }
           if (cursor + 1 < kcount) ++cursor;   // past the end: surplus loads repeat the last step
-          const int64_t koff = (int64_t)kstep * (kTileK * 2);
-          src.gP = P + koff;
-          src.gQ = Q + koff;
+          src.gP = P;
+          laneP.offsets(kstep * kTileK, kP_last, ldP, src.offP);
+          if (DC) {
+            src.gQ = Q;
+            laneQ.offsets(kstep * kTileK, sl.Np - 1, ldQ, src.offQ);
+          } else {
+            src.gQ = Q + (int64_t)kstep * (kTileK * 2);
 #pragma unroll
-          for (int j = 0; j < 4; ++j) { src.offP[j] = offP[j]; src.offQ[j] = offQ[j]; }
+            for (int j = 0; j < 4; ++j) src.offQ[j] = offQ[j];
+          }
         },
         [&](int) {});
   }
@@ -335,14 +321,6 @@ __global__ void zero_u32_kernel(uint32_t* p, int64_t count) {
 }
 
 }  // namespace
-
-hipError_t launch_transpose_bf16(const bf16* in, int rows_valid, int rows_padded, int cols, int64_t ld_in,
-                                 bf16* out, hipStream_t stream) {
-  dim3 grid(rows_padded / 64, (cols + 63) / 64);
-  hipLaunchKernelGGL(transpose_bf16_kernel, grid, dim3(256), 0, stream, (const uint16_t*)in, rows_valid,
-                     rows_padded, cols, ld_in, (uint16_t*)out);
-  return hipGetLastError();
-}
 
 hipError_t launch_bwd_recompute_mfma(const BwdCommon& c, const BwdMfmaSlab& s, hipStream_t stream) {
   const int n_tiles = s.Np / kTileC, v_tiles = s.vs / kTileR;

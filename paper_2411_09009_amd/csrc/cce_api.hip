@@ -91,7 +91,6 @@ struct Helpers {
   hipStream_t product[3] = {};        // [0], [2] dC products of even / odd slabs, [1] dE products
   hipEvent_t started = nullptr;
   hipEvent_t recomputed[kEventRing] = {};
-  hipEvent_t gathered[kEventRing] = {};
   hipEvent_t dC_done[kEventRing] = {};
   hipEvent_t dE_done[kEventRing] = {};
 };
@@ -108,7 +107,6 @@ int helpers_for_device(Helpers** out) {
     CCE_HIP(hipEventCreateWithFlags(&h.started, hipEventDisableTiming));
     for (int i = 0; i < kEventRing; ++i) {
       CCE_HIP(hipEventCreateWithFlags(&h.recomputed[i], hipEventDisableTiming));
-      CCE_HIP(hipEventCreateWithFlags(&h.gathered[i], hipEventDisableTiming));
       CCE_HIP(hipEventCreateWithFlags(&h.dC_done[i], hipEventDisableTiming));
       CCE_HIP(hipEventCreateWithFlags(&h.dE_done[i], hipEventDisableTiming));
     }
@@ -171,7 +169,7 @@ FwdPlan plan_forward(int64_t N, int64_t D, int64_t V, const cce_opts* o) {
 struct BwdPlan {
   bool mfma;
   int64_t Np, vs;          // padded token count, slab width
-  size_t off_flags[kSlabBuffers], off_dEacc, off_ET, off_CT[kSlabBuffers], off_GZ[kSlabBuffers], off_GZT[kSlabBuffers];   // one set per slab in flight (MFMA path)
+  size_t off_flags[kSlabBuffers], off_dEacc, off_GZ[kSlabBuffers];   // flags, GZ: one per slab in flight (MFMA path)
   // vocabulary sorting (MFMA path only)
   size_t off_partial, off_mean, off_key, off_key_sorted, off_index, off_perm, off_inverse, off_targets, off_Cs[kSlabBuffers],
       off_sort_temp;
@@ -188,16 +186,10 @@ BwdPlan layout_backward(bool mfma, int64_t N, int64_t D, int64_t V, int64_t vs, 
     p.Np = round_up(N, 256);
     p.off_dEacc = off;
     off += align_up((size_t)N * D * 4, 256);
-    p.off_ET = off;
-    off += align_up((size_t)D * p.Np * 2, 256);
     for (int b = 0; b < kSlabBuffers; ++b) {
       p.off_flags[b] = off;
       off += align_up(((size_t)(p.Np / 256) * (vs / 64) + (size_t)(vs / 256) * (p.Np / 64)) * 4, 256);
-      p.off_CT[b] = off;
-      off += align_up((size_t)D * vs * 2, 256);
       p.off_GZ[b] = off;
-      off += align_up((size_t)p.Np * vs * 2, 256);
-      p.off_GZT[b] = off;
       off += align_up((size_t)p.Np * vs * 2, 256);
     }
     if (sort) {
@@ -375,13 +367,11 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
     std::lock_guard<std::mutex> lock(h->mutex);
     BwdMfmaSlab s{};
     s.Np = (int)plan.Np;
-    s.ET = (bf16*)(ws + plan.off_ET);
     s.dEacc = dEacc;
     // a filtered contraction keeps its list of 64-wide steps in LDS; longer ones run unfiltered
     if (plan.Np / 64 > kMaxFilteredKSteps) c.filter_dC = 0;
     // helper work may not start before the caller's earlier work on `stream` (which may produce C)
     CCE_HIP(hipEventRecord(h->started, stream));
-    CCE_HIP(launch_transpose_bf16((const bf16*)E, (int)N, (int)plan.Np, (int)D, D, s.ET, stream));
     if (sort) {
       VocabSortParams v{};
       v.E = (const bf16*)E; v.C = (const bf16*)C; v.targets = targets;
@@ -409,9 +399,7 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
       s.v0 = (int)v0;
       s.vs = (int)vs_this;
       s.first = v0 == 0;
-      s.CT = (bf16*)(ws + plan.off_CT[b]);
       s.GZ = (bf16*)(ws + plan.off_GZ[b]);
-      s.GZT = (bf16*)(ws + plan.off_GZT[b]);
       s.flags_nv = (uint32_t*)(ws + plan.off_flags[b]);
       s.flags_vn = s.flags_nv + (plan.Np / 256) * (vs_this / 64);
       if (slab >= kSlabBuffers) {
@@ -424,10 +412,9 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
       s.Crows = (const bf16*)C + v0 * D;
       if (sort) {
         // the slab's rows of C, gathered in sorted order (its buffer was last read by the
-        // recompute and the transpose of slab - 2, both waited for above)
+        // recompute and the dE product of the slab that used it before, both waited for above)
         bf16* Cs = (bf16*)(ws + plan.off_Cs[b]);
         CCE_HIP(launch_gather_rows((const bf16*)C, s.perm, (int)v0, (int)rows_valid, (int)D, Cs, stream));
-        CCE_HIP(hipEventRecord(h->gathered[e], stream));
         s.Crows = Cs;
       }
       CCE_HIP(launch_bwd_recompute_mfma(c, s, stream));
@@ -441,13 +428,8 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
       CCE_HIP(hipStreamWaitEvent(dC_stream, h->recomputed[e], 0));
       CCE_HIP(launch_bwd_dC_mfma(c, s, out_dC, dC_stream));
       CCE_HIP(hipEventRecord(h->dC_done[e], dC_stream));
-      // The transposed C slab is needed by the dE product only, so it is made on that
-      // product's stream, ahead of the recompute it would otherwise delay (its buffer was
-      // last read by the dE product of slab - 2, earlier on the same stream).  dEacc is
-      // read-modify-written slab after slab: stream order keeps that sequence.
+      // dEacc is read-modify-written slab after slab: stream order keeps that sequence
       if (slab == 0) CCE_HIP(hipStreamWaitEvent(dE_stream, h->started, 0));
-      if (sort) CCE_HIP(hipStreamWaitEvent(dE_stream, h->gathered[e], 0));
-      CCE_HIP(launch_transpose_bf16(s.Crows, (int)rows_valid, (int)vs_this, (int)D, D, s.CT, dE_stream));
       CCE_HIP(hipStreamWaitEvent(dE_stream, h->recomputed[e], 0));
       CCE_HIP(launch_bwd_dE_mfma(c, s, dE_stream));
       CCE_HIP(hipEventRecord(h->dE_done[e], dE_stream));

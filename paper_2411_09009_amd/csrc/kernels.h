@@ -117,10 +117,7 @@ struct BwdCommon {
 // MFMA path buffers (bf16).  Np = N rounded up to 256.
 struct BwdMfmaSlab {
   int v0, vs, Np;
-  bf16* ET;             // [D, Np]   E transposed, zero beyond N (filled once per call)
-  bf16* CT;             // [D, vs]   slab of C transposed, zero beyond V
-  bf16* GZ;             // [Np, vs]  dloss * G * a'   (token-major)
-  bf16* GZT;            // [vs, Np]  the same, vocabulary-major
+  bf16* GZ;             // [Np, vs]  dloss * G * a'   (token-major; zero for tokens >= N and columns >= V)
   float* dEacc;         // [N, D]
   uint32_t* flags_nv;   // [Np/256, vs/64]  block (256 tokens x 64 vocab) has a significant entry
   uint32_t* flags_vn;   // [vs/256, Np/64]  block (64 tokens x 256 vocab) has a significant entry;
@@ -131,8 +128,6 @@ struct BwdMfmaSlab {
   const int* perm;      // sorted position -> original vocabulary index (rows of dC are written
                         // through it); nullptr = identity
 };
-hipError_t launch_transpose_bf16(const bf16* in, int rows_valid, int rows_padded, int cols, int64_t ld_in,
-                                 bf16* out, hipStream_t stream);
 hipError_t launch_bwd_recompute_mfma(const BwdCommon& c, const BwdMfmaSlab& s, hipStream_t stream);
 hipError_t launch_bwd_dE_mfma(const BwdCommon& c, const BwdMfmaSlab& s, hipStream_t stream);
 hipError_t launch_bwd_dC_mfma(const BwdCommon& c, const BwdMfmaSlab& s, void* out_dC, hipStream_t stream);

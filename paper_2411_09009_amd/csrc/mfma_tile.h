@@ -26,6 +26,14 @@
 // writes bytes [16 i, 16 i + 16) of a 1 KB span), the swizzle is applied on the
 // global side: lane i fetches the chunk that belongs at its position.
 //
+// An operand whose contracted index is NOT contiguous in memory ("K-major": rows are K
+// steps, 256 output rows or columns contiguous, as E and GZ are when the contraction runs
+// over tokens) is staged as 64 K-rows of 512 B and its fragments are fetched with
+// ds_read_b64_tr_b16: sixteen lanes read a 4 (K) x 16 block as four 8-byte pieces per row
+// and each receives four consecutive K values of one column, so two such reads make one
+// MFMA operand.  Chunk c of K-row k sits at position c ^ (4 * (k & 3)), which spreads the
+// four rows a 16-lane group touches over all banks.
+//
 // LDS reads are issued through inline assembly with explicit s_waitcnt: the
 // compiler does not see them as LDS accesses, so it does not serialise them
 // against the direct loads still in flight for the other stage.  All waits are
@@ -55,6 +63,20 @@ constexpr int kRB = 4, kCB = 2;    // 32x32 blocks per wave along rows / columns
 
 __device__ inline uint32_t lds_addr(const void* p) { return (uint32_t)(uintptr_t)CCE_LDS_PTR(p); }
 
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Eight consecutive K values of this lane's column from a K-major slice: two transposing
+// reads, K rows IMM/512 .. +3 and +4 .. +7 relative to `addr`.
+template <int IMM>
+__device__ inline bf16x8 lds_read_tr(uint32_t addr) {
+  u32x2 lo, hi;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(addr), "n"(IMM));
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(addr), "n"(IMM + 2048));
+  u32x4 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
 template <int IMM>
 __device__ inline bf16x8 lds_read_b128(uint32_t addr) {
   bf16x8 v;
@@ -76,6 +98,9 @@ struct TileCoords {
   // LDS byte offsets (relative to a stage's start) of this lane's P row and Q
   // row at each of the four 16-deep MFMA steps of a stage, swizzle included
   uint32_t p_off[4], q_off[4];
+  // the same for K-major slices: byte offset of the lane's 8-byte piece in the first K-row
+  // group of a stage, per 32-wide block of the wave (later K steps are immediate offsets)
+  uint32_t pk_off[kRB], qk_off[kCB];
   __device__ void init() {
     lane = threadIdx.x & 63;
     wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -89,6 +114,48 @@ struct TileCoords {
       uint32_t k = ((uint32_t)(ks * 2) ^ x) * 16u;
       p_off[ks] = p_row + k;
       q_off[ks] = q_row + k;
+    }
+    // K-major: lane = (column c = lane & 31, K half kg = lane >> 5); as a source lane of its
+    // 16-lane group it reads K-row (s >> 2) and columns 4 (s & 3) .. +3 of the group's 16
+    const uint32_t s16 = (uint32_t)(lane & 15), half = (uint32_t)((lane >> 4) & 1), kg = (uint32_t)(lane >> 5);
+    const uint32_t krow = 8u * kg + (s16 >> 2), swz = 4u * (s16 >> 2);
+#pragma unroll
+    for (int rb = 0; rb < kRB; ++rb) {
+      uint32_t chunk = (uint32_t)(wave_r * kWaveRows + rb * 32) / 8u + 2u * half + ((s16 & 3u) >> 1);
+      pk_off[rb] = krow * 512u + ((chunk ^ swz) << 4) + 8u * (s16 & 1u);
+    }
+#pragma unroll
+    for (int cb = 0; cb < kCB; ++cb) {
+      uint32_t chunk = (uint32_t)(wave_c * kWaveCols + cb * 32) / 8u + 2u * half + ((s16 & 3u) >> 1);
+      qk_off[cb] = krow * 512u + ((chunk ^ swz) << 4) + 8u * (s16 & 1u) + kSliceBytes;
+    }
+  }
+};
+
+// K-major operand: the lane's constants for the four 16-byte chunks it brings in per stage.
+// DMA instruction ii = wave * 4 + j covers K-rows 2 ii and 2 ii + 1 (32 chunks each); lane
+// i fills position i & 31 of row 2 ii + (i >> 5), i.e. logical chunk (i & 31) ^ (4 * (k & 3)).
+struct KMajorLane {
+  uint32_t krow0;        // K-row of j = 0 (row of j is krow0 + 2 j)
+  uint32_t col[2];       // byte offset of the chunk inside the row for even / odd j
+  __device__ void init(const TileCoords& tc, int chunks_valid) {
+    krow0 = (uint32_t)(tc.wave * 8 + (tc.lane >> 5));
+#pragma unroll
+    for (int par = 0; par < 2; ++par) {
+      uint32_t k = krow0 + 2u * par;
+      int c = (int)(((uint32_t)tc.lane & 31u) ^ (4u * (k & 3u)));
+      if (c >= chunks_valid) c = chunks_valid - 1;     // columns past the operand's width: duplicates, discarded later
+      col[par] = (uint32_t)c * 16u;
+    }
+  }
+  // offsets (from the operand tile's origin: row 0, first column of the tile) for the stage
+  // that starts at K-row k0; K-rows past k_last are clamped to it
+  __device__ void offsets(int k0, int k_last, uint32_t ld_bytes, uint32_t (&off)[4]) const {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int k = k0 + (int)krow0 + 2 * j;
+      k = k < k_last ? k : k_last;
+      off[j] = (uint32_t)k * ld_bytes + col[j & 1];
     }
   }
 };
@@ -130,16 +197,29 @@ __device__ inline void dma_stage(const TileCoords& tc, const StageSrc& src, char
   for (int j = 0; j < 4; ++j) dma_one(tc, src.gQ, src.offQ[j], lds_stage + kSliceBytes, j);
 }
 
-#define CCE_READ_FRAGS(buf, addr, ks)                                  \
-  {                                                                    \
-    uint32_t pa = (addr) + tc.p_off[ks], qa = (addr) + tc.q_off[ks];   \
-    p[buf][0] = lds_read_b128<0>(pa);                                  \
-    p[buf][1] = lds_read_b128<4096>(pa);                               \
-    p[buf][2] = lds_read_b128<8192>(pa);                               \
-    p[buf][3] = lds_read_b128<12288>(pa);                              \
-    q[buf][0] = lds_read_b128<0>(qa);                                  \
-    q[buf][1] = lds_read_b128<4096>(qa);                               \
+// Issue the fragment reads of 16-deep step KS of the stage at LDS address `addr`.
+template <bool PK, bool QK, int KS>
+__device__ inline void read_frags(const TileCoords& tc, uint32_t addr, bf16x8 (&p)[kRB], bf16x8 (&q)[kCB]) {
+  if constexpr (PK) {
+#pragma unroll
+    for (int rb = 0; rb < kRB; ++rb) p[rb] = lds_read_tr<KS * 16 * 512>(addr + tc.pk_off[rb]);
+  } else {
+    const uint32_t pa = addr + tc.p_off[KS];
+    p[0] = lds_read_b128<0>(pa);
+    p[1] = lds_read_b128<4096>(pa);
+    p[2] = lds_read_b128<8192>(pa);
+    p[3] = lds_read_b128<12288>(pa);
   }
+  if constexpr (QK) {
+#pragma unroll
+    for (int cb = 0; cb < kCB; ++cb) q[cb] = lds_read_tr<KS * 16 * 512>(addr + tc.qk_off[cb]);
+  } else {
+    const uint32_t qa = addr + tc.q_off[KS];
+    q[0] = lds_read_b128<0>(qa);
+    q[1] = lds_read_b128<4096>(qa);
+  }
+}
+#define CCE_READ_FRAGS(buf, addr, ks) read_frags<PK, QK, ks>(tc, addr, p[buf], q[buf]);
 
 // Orders every MFMA that follows after the volatile asm statements that precede (the
 // fragment reads just issued): without it the compiler sinks the reads below the MFMAs
@@ -170,7 +250,8 @@ __device__ inline void pin_acc(f32x16 (&acc)[kRB][kCB]) {
 // dead, so the loads of stage i+2 are issued into it, interleaved with group 3's MFMAs so
 // that their address-queue back-pressure never delays an MFMA.  Each load has one full
 // stage to arrive.
-template <class Next, class StepDone>
+// PK / QK: the P / Q operand is K-major (see the top of this file).
+template <bool PK = false, bool QK = false, class Next, class StepDone>
 __device__ inline void mma_pipeline(const TileCoords& tc, char* lds, int nsteps, f32x16 (&acc)[kRB][kCB], Next next,
                                     StepDone step_done) {
   if (nsteps <= 0) return;
