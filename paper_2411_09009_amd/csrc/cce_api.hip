@@ -32,7 +32,7 @@ inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
 constexpr int kMaxDevices = 64;
-constexpr int64_t kMfmaSlabCols = 8192;  // recommended backward slab width (vocabulary entries), MFMA path
+constexpr int64_t kMfmaSlabCols = 6144;  // recommended backward slab width (vocabulary entries), MFMA path
 constexpr int64_t kPlainSlabCols = 4096;
 constexpr int kMaxFilteredKSteps = 2048;
 constexpr int kSlabBuffers = 2;          // vocabulary slabs in flight in the MFMA backward pass
