@@ -139,16 +139,36 @@ def main():
     ms_per_step = wall_ms / args.steps
 
     # filtered backward (the library default), reported beside the dense one
-    for _ in range(2):
-        bwd(ob_filt)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(args.steps):
-        bwd(ob_filt)
-    e1.record()
-    torch.cuda.synchronize()
-    bwd_filt_ms = e0.elapsed_time(e1) / args.steps
+    def timed(fn):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / args.steps
+
+    # the paper's method proper: gradient filtering on; with CCE_SKIP_TILES the forward also
+    # records per-block logit maxima and the backward recomputes only tiles the filter can keep
+    both = L.CCE_FILTER_DE | L.CCE_FILTER_DC
+    bm = torch.empty(L.cce_block_max_bytes(N, V), dtype=torch.uint8, device=dev)
+    o_s = L.make_opts(L.CCE_BF16, flags=both | L.CCE_SKIP_TILES)
+    ws_bs = torch.empty(L.cce_workspace_bytes(L.CCE_OP_BACKWARD, N, D, V, o_s), dtype=torch.uint8, device=dev)
+    of_rec = L.make_opts(L.CCE_BF16, flags=both | L.CCE_SKIP_TILES, workspace=ws_f, block_max=bm)
+    ob_skip = L.make_opts(L.CCE_BF16, flags=both | L.CCE_SKIP_TILES, workspace=ws_bs, block_max=bm)
+
+    def fwd_rec():
+        L.cce_forward_ex(E, C, tg, w.softcap, w.ignore_index, of_rec, out_loss=loss, out_lse=lse)
+
+    fwd_rec_ms = timed(fwd_rec)
+    bwd_skip_ms = timed(lambda: bwd(ob_skip))
+    dE_s, dC_s = dE.clone(), dC.clone()
+    bwd_filt_ms = timed(lambda: bwd(ob_filt))
+    skip_identical = bool(torch.equal(dE_s, dE) and torch.equal(dC_s, dC))
+    del dE_s, dC_s
     total, kept = L.cce_backward_filter_stats(ws_b)
     dE_f, dC_f = dE.float().clone(), dC.float()
     bwd(ob_dense)
@@ -182,6 +202,9 @@ def main():
         "frac_mfma_peak_fwd_bwd": (4.0 * fwd_flop / (ms_per_step * 1e-3) / 1e12) / MFMA_BF16_PEAK_TFLOPS,
         "bwd_filtered": {"ms": bwd_filt_ms, "blocks_kept": kept, "blocks_total": total,
                          "dE_rel_fro_vs_dense": err_dE, "dC_rel_fro_vs_dense": err_dC},
+        "filtered_skip_tiles": {"fwd_with_record_ms": fwd_rec_ms, "bwd_ms": bwd_skip_ms,
+                                "fwd_bwd_tokens_per_s": N / ((fwd_rec_ms + bwd_skip_ms) * 1e-3),
+                                "record_bytes": bm.numel(), "bit_identical_to_filtered": skip_identical},
         "extra_hbm_bytes": {"forward_workspace": fwd_bytes, "backward_workspace": bwd_bytes,
                             "logits_avoided_fp32": 4 * N * V},
         "roofline": {"kernel": "fwd_lse_mfma_kernel (timed as cce_forward_ex: + finalize, <1%)",

@@ -65,8 +65,17 @@ enum {
                                 fp32 summation order of dE).  bf16 MFMA path only (CCE_EUNSUPPORTED
                                 otherwise); costs O(|V|) extra workspace plus two slab-sized copies of C
                                 rows.  The forward pass ignores the flag. */
-  CCE_PLAIN_KERNELS = 1u << 3 /* run the plain fp32-FMA kernels instead of the MFMA ones (always used
+  CCE_PLAIN_KERNELS = 1u << 3, /* run the plain fp32-FMA kernels instead of the MFMA ones (always used
                                 for CCE_F32 and for shapes the MFMA kernels do not take) */
+  CCE_SKIP_TILES = 1u << 4    /* forward: also record, in opts->block_max, the largest logit of every token
+                                within each 128-wide vocabulary block; backward (with both CCE_FILTER_* set
+                                and filter_eps > 0): do not even recompute the logit tiles in which that
+                                record shows no softmax entry can reach filter_eps and which hold no target.
+                                The gradients are bit-identical to the filtered backward without the flag
+                                (only tiles whose blocks the filter drops anyway are left out); Alg. 3 / 4
+                                recompute every tile first and test afterwards.  bf16 MFMA path only; ignored
+                                together with CCE_VOCAB_SORT (the record is in forward vocabulary order).
+                                Costs 2 * |V| / 128 bytes per token (cce_block_max_bytes). */
 };
 
 /* cce_workspace_bytes(op, ...) */
@@ -84,6 +93,10 @@ typedef struct cce_opts {
   void* workspace;        /* device scratch, 256-byte aligned, owned by the caller */
   size_t workspace_bytes;
   void* stream;           /* hipStream_t; NULL = null stream */
+  void* block_max;        /* CCE_SKIP_TILES: device buffer of cce_block_max_bytes(N, V) bytes, 256-byte
+                             aligned, owned by the caller; written by the forward call, read by the
+                             backward call on the same inputs.  NULL = the flag has no effect. */
+  size_t block_max_bytes;
 } cce_opts;
 
 /* Fills *opts with the defaults the plain entry points use for `dtype`:
@@ -145,6 +158,9 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets,
 /* Workspace size in bytes for `op` (CCE_OP_*) at this shape and these options
  * (dtype and flags are read; workspace fields are not).  0 on invalid arguments. */
 size_t cce_workspace_bytes(int op, int64_t N, int64_t D, int64_t V, const cce_opts* opts);
+
+/* Size in bytes of the block-maximum record of CCE_SKIP_TILES; 0 on invalid arguments. */
+size_t cce_block_max_bytes(int64_t N, int64_t V);
 
 /* Rows (tokens) x columns (vocabulary entries) of the block the gradient filter
  * tests as a unit, for the kernels `opts` selects at this shape. */

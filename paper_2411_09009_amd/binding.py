@@ -10,7 +10,7 @@ import torch
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libcce.so")
 
 CCE_BF16, CCE_F32 = 0, 1
-CCE_FILTER_DE, CCE_FILTER_DC, CCE_VOCAB_SORT, CCE_PLAIN_KERNELS = 1, 2, 4, 8
+CCE_FILTER_DE, CCE_FILTER_DC, CCE_VOCAB_SORT, CCE_PLAIN_KERNELS, CCE_SKIP_TILES = 1, 2, 4, 8, 16
 CCE_OP_FORWARD, CCE_OP_BACKWARD, CCE_OP_BACKWARD_MIN = 0, 1, 2
 
 
@@ -22,6 +22,8 @@ class CceOpts(ctypes.Structure):
         ("workspace", ctypes.c_void_p),
         ("workspace_bytes", ctypes.c_size_t),
         ("stream", ctypes.c_void_p),
+        ("block_max", ctypes.c_void_p),
+        ("block_max_bytes", ctypes.c_size_t),
     ]
 
 
@@ -52,6 +54,8 @@ def load() -> ctypes.CDLL:
     lib.cce_strerror.restype = ctypes.c_char_p
     lib.cce_workspace_bytes.argtypes = [ctypes.c_int, i64, i64, i64, po]
     lib.cce_workspace_bytes.restype = sz
+    lib.cce_block_max_bytes.argtypes = [i64, i64]
+    lib.cce_block_max_bytes.restype = sz
     lib.cce_filter_block.argtypes = [i64, i64, i64, po, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
     lib.cce_filter_block.restype = None
     fwd = [vp, vp, vp, i64, i64, i64, f32, i64, vp, vp]
@@ -96,7 +100,8 @@ def _dtype_code(t: torch.Tensor) -> int:
 
 
 def make_opts(dtype: int, flags: Optional[int] = None, filter_eps: Optional[float] = None,
-              workspace: Optional[torch.Tensor] = None, stream: Optional[int] = None) -> CceOpts:
+              workspace: Optional[torch.Tensor] = None, stream: Optional[int] = None,
+              block_max: Optional[torch.Tensor] = None) -> CceOpts:
     """Defaults of the plain entry points, overridden by the arguments given."""
     o = cce_default_opts(dtype)
     if flags is not None:
@@ -106,12 +111,19 @@ def make_opts(dtype: int, flags: Optional[int] = None, filter_eps: Optional[floa
     if workspace is not None:
         o.workspace = workspace.data_ptr()
         o.workspace_bytes = workspace.numel() * workspace.element_size()
+    if block_max is not None:
+        o.block_max = block_max.data_ptr()
+        o.block_max_bytes = block_max.numel() * block_max.element_size()
     o.stream = torch.cuda.current_stream().cuda_stream if stream is None else int(stream)
     return o
 
 
 def cce_workspace_bytes(op: int, N: int, D: int, V: int, opts: CceOpts) -> int:
     return int(load().cce_workspace_bytes(int(op), int(N), int(D), int(V), ctypes.byref(opts)))
+
+
+def cce_block_max_bytes(N: int, V: int) -> int:
+    return int(load().cce_block_max_bytes(int(N), int(V)))
 
 
 def cce_filter_block(N: int, D: int, V: int, opts: CceOpts) -> Tuple[int, int]:

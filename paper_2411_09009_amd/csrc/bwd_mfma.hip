@@ -23,47 +23,118 @@ namespace cce {
 
 namespace {
 
+// ------------------------------------------------------------------ tiles that cannot be skipped
+// A 256-token x 256-vocabulary tile needs recomputing only if some valid token of it has a
+// softmax entry that can reach the filter threshold, S_ij = exp(a_ij - lse_i) >= eps, or has
+// its target inside the tile (|G| = 1 - S there).  max_j a_ij over 128-wide blocks comes from
+// the forward pass (rounded up), so the test never skips a tile the filter would keep.
+__global__ __launch_bounds__(256) void tile_flag_kernel(TileListParams p) {
+  const int vt = blockIdx.x, nt = blockIdx.y;
+  const int tok = nt * 256 + threadIdx.x;
+  bool sig = false;
+  if (tok < p.N) {
+    const int64_t t = p.targets[tok];
+    if (t != p.ignore_index && t >= 0 && t < p.V) {
+      const int b0 = vt * 2, blocks = (p.V + 127) / 128;
+      uint32_t u0 = p.block_max[(int64_t)b0 * p.stride + tok];
+      float a = __uint_as_float(u0 << 16);
+      if (b0 + 1 < blocks) {
+        uint32_t u1 = p.block_max[(int64_t)(b0 + 1) * p.stride + tok];
+        a = fmaxf(a, __uint_as_float(u1 << 16));
+      }
+      sig = (a - p.lse[tok] >= p.log_eps) || (t >= (int64_t)vt * 256 && t < (int64_t)vt * 256 + 256);
+    }
+  }
+  const bool any = __syncthreads_or(sig);
+  if (threadIdx.x == 0) p.tile_flag[(int64_t)nt * p.v_tiles + vt] = any ? 1 : 0;
+}
+
+// one workgroup per slab: compact the slab's flagged tiles, token-tile major
+__global__ __launch_bounds__(256) void tile_compact_kernel(TileListParams p) {
+  __shared__ int wave_count[4];
+  __shared__ int base_s;
+  const int slab = blockIdx.x;
+  const int vt0 = slab * p.slab_tiles;
+  const int tiles_here = min(p.slab_tiles, p.v_tiles - vt0);
+  const int total = p.n_tiles * tiles_here;
+  uint32_t* list = p.tile_list + (int64_t)slab * p.n_tiles * p.slab_tiles;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (threadIdx.x == 0) base_s = 0;
+  __syncthreads();
+  for (int i0 = 0; i0 < total; i0 += 256) {
+    const int i = i0 + threadIdx.x;
+    const int nt = i / tiles_here, tl = i % tiles_here;
+    const bool on = i < total && p.tile_flag[(int64_t)nt * p.v_tiles + vt0 + tl] != 0;
+    const uint64_t mask = __builtin_amdgcn_ballot_w64(on);
+    if (lane == 0) wave_count[wave] = __builtin_popcountll(mask);
+    __syncthreads();
+    int pos = base_s + __builtin_popcountll(mask & ((1ull << lane) - 1ull));
+    for (int w = 0; w < wave; ++w) pos += wave_count[w];
+    if (on) list[pos] = ((uint32_t)nt << 16) | (uint32_t)tl;
+    __syncthreads();
+    if (threadIdx.x == 0) base_s += wave_count[0] + wave_count[1] + wave_count[2] + wave_count[3];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) p.tile_count[slab] = (uint32_t)base_s;
+}
+
 enum { kNoCap = 0, kCap = 1 };
 constexpr int kMaxKSteps = 2048;   // longest filtered contraction: 131072 / 64
 
 // ------------------------------------------------------------------ recompute + G
-template <int MODE>
+// LIST: the workgroup takes an equal share of the slab's work list (tiles the filter cannot
+// skip) instead of a fixed rectangle of tiles.
+template <int MODE, bool LIST>
 __global__ __launch_bounds__(kThreads) void bwd_recompute_mfma_kernel(BwdCommon c, BwdMfmaSlab sl, XcdMap map,
                                                                       int tiles_per_split) {
   __shared__ __attribute__((aligned(1024))) char lds[kLdsBytes + 8 * 4096];   // operand ring + store staging
   TileCoords tc;
   tc.init();
-  int n_tile, split;
-  if (!xcd_map_decode(map, blockIdx.x, n_tile, split)) return;
   const int v_tiles = sl.vs / kTileR;
-  const int t0 = split * tiles_per_split, t1 = min(t0 + tiles_per_split, v_tiles);
-  const int n0 = n_tile * kTileC;
   const int64_t ld_bytes = (int64_t)c.D * 2;
   const int KT = c.D / kTileK;
+  int n_tile = 0, t0 = 0, t1 = 0;   // fixed rectangle: token tile and vocabulary tile range
+  int e0 = 0, e1 = 0;               // work list: entry range
+  if (LIST) {
+    // consecutive entries share a token tile: give each XCD a run of consecutive shares
+    const int groups = (int)gridDim.x, per_xcd = groups / kXcds;
+    const int logical = ((int)blockIdx.x % kXcds) * per_xcd + (int)blockIdx.x / kXcds;
+    const int count = (int)*sl.tile_count;
+    const int share = (count + groups - 1) / groups;
+    e0 = logical * share;
+    e1 = min(e0 + share, count);
+    if (e0 >= e1) return;
+    n_tile = (int)(sl.tile_list[e0] >> 16);
+  } else {
+    int split;
+    if (!xcd_map_decode(map, blockIdx.x, n_tile, split)) return;
+    t0 = split * tiles_per_split;
+    t1 = min(t0 + tiles_per_split, v_tiles);
+  }
+  int n0 = n_tile * kTileC;
 
-  uint32_t offQ[4];
-  dma_offsets(tc, min(kTileC, c.N - n0), ld_bytes, offQ);
-  const char* gQ = (const char*)c.E + (int64_t)n0 * ld_bytes;
-
-  // per-lane token data for the lane's two token columns
+  // per-lane token data for the lane's two token columns of token tile `n_tile`
   float lse2[kCB], lam[kCB];
   int tgt[kCB], ncol[kCB];
+  auto load_tokens = [&]() {
 #pragma unroll
-  for (int cb = 0; cb < kCB; ++cb) {
-    const int n = n0 + tc.wave_c * kWaveCols + cb * 32 + (tc.lane & 31);
-    ncol[cb] = n;
-    lse2[cb] = 0.f;
-    lam[cb] = 0.f;
-    tgt[cb] = -1;
-    if (n < c.N) {
-      const int64_t t = c.targets[n];
-      if (t != c.ignore_index && t >= 0 && t < c.V) {
-        tgt[cb] = (int)t;
-        lam[cb] = c.dloss[n];
-        lse2[cb] = c.lse[n] * kLog2e;
+    for (int cb = 0; cb < kCB; ++cb) {
+      const int n = n0 + tc.wave_c * kWaveCols + cb * 32 + (tc.lane & 31);
+      ncol[cb] = n;
+      lse2[cb] = 0.f;
+      lam[cb] = 0.f;
+      tgt[cb] = -1;
+      if (n < c.N) {
+        const int64_t t = c.targets[n];
+        if (t != c.ignore_index && t >= 0 && t < c.V) {
+          tgt[cb] = (int)t;
+          lam[cb] = c.dloss[n];
+          lse2[cb] = c.lse[n] * kLog2e;
+        }
       }
     }
-  }
+  };
+  load_tokens();
 
   f32x16 acc[kRB][kCB];
 #pragma unroll
@@ -92,7 +163,7 @@ __global__ __launch_bounds__(kThreads) void bwd_recompute_mfma_kernel(BwdCommon 
   // read side: instruction rr covers rows rr * 8 + lane / 8, logical chunk lane % 8
   const uint32_t rd_row = (uint32_t)(tc.lane >> 3), rd_chunk = (uint32_t)(tc.lane & 7);
 
-  sweep_tiles(tc, lds, P, c.V - sl.v0, ld_bytes, t0, t1, gQ, offQ, KT, acc, [&](int t) {
+  auto epilogue = [&](int t) {
     const int vl_base = t * kTileR + tc.wave_r * kWaveRows;   // slab-local vocabulary row of this wave
     bool sig[2] = {false, false};                              // halves rb {0,1} and {2,3}
 #pragma unroll
@@ -163,7 +234,37 @@ __global__ __launch_bounds__(kThreads) void bwd_recompute_mfma_kernel(BwdCommon 
       if (any1) atomicOr(f_nv + 1, 1u);
       if (any0 || any1) atomicOr(sl.flags_vn + (int64_t)t * (sl.Np / 64) + n_tile * 4 + tc.wave_c, 1u);
     }
-  });
+    return true;   // the 16 staged stores (and up to 3 flag updates after them) are this wave's last memory operations
+  };
+
+  if (LIST) {
+    const int slab_rows = c.V - sl.v0;
+    sweep_entries<16>(
+        tc, lds, e0, e1, KT, acc,
+        [&](int e, const char*& gP, uint32_t (&offP)[4], const char*& gQ, uint32_t (&offQ)[4]) {
+          const uint32_t entry = sl.tile_list[e];
+          const int nt = (int)(entry >> 16), tl = (int)(entry & 0xffffu);
+          gP = P + (int64_t)tl * kTileR * ld_bytes;
+          dma_offsets(tc, min(kTileR, slab_rows - tl * kTileR), ld_bytes, offP);
+          gQ = (const char*)c.E + (int64_t)nt * kTileC * ld_bytes;
+          dma_offsets(tc, min(kTileC, c.N - nt * kTileC), ld_bytes, offQ);
+        },
+        [&](int e) {
+          const uint32_t entry = sl.tile_list[e];
+          const int nt = (int)(entry >> 16);
+          if (nt != n_tile) {
+            n_tile = nt;
+            n0 = nt * kTileC;
+            load_tokens();
+          }
+          return epilogue((int)(entry & 0xffffu));
+        });
+  } else {
+    uint32_t offQ[4];
+    dma_offsets(tc, min(kTileC, c.N - n0), ld_bytes, offQ);
+    const char* gQ = (const char*)c.E + (int64_t)n0 * ld_bytes;
+    sweep_tiles<16>(tc, lds, P, c.V - sl.v0, ld_bytes, t0, t1, gQ, offQ, KT, acc, epilogue);
+  }
 }
 
 // ------------------------------------------------------------------ gradient products
@@ -251,7 +352,7 @@ __global__ __launch_bounds__(kThreads) void bwd_product_mfma_kernel(BwdCommon c,
             for (int j = 0; j < 4; ++j) src.offQ[j] = offQ[j];
           }
         },
-        [&](int) {});
+        [&](int) { return false; });
   }
 
   // rows of dC go back to their original vocabulary index when the slab was walked in sorted order
@@ -322,6 +423,12 @@ __global__ void zero_u32_kernel(uint32_t* p, int64_t count) {
 
 }  // namespace
 
+hipError_t launch_tile_lists(const TileListParams& p, hipStream_t stream) {
+  hipLaunchKernelGGL(tile_flag_kernel, dim3(p.v_tiles, p.n_tiles), dim3(256), 0, stream, p);
+  hipLaunchKernelGGL(tile_compact_kernel, dim3(p.slabs), dim3(256), 0, stream, p);
+  return hipGetLastError();
+}
+
 hipError_t launch_bwd_recompute_mfma(const BwdCommon& c, const BwdMfmaSlab& s, hipStream_t stream) {
   const int n_tiles = s.Np / kTileC, v_tiles = s.vs / kTileR;
   // clear the slab's flags
@@ -335,11 +442,22 @@ hipError_t launch_bwd_recompute_mfma(const BwdCommon& c, const BwdMfmaSlab& s, h
   int tps = (v_tiles + splits - 1) / splits;
   splits = (v_tiles + tps - 1) / tps;
   const XcdMap map = make_xcd_map(n_tiles, splits);
-  dim3 grid(xcd_map_grid(map));
-  if (c.softcap > 0.f)
-    hipLaunchKernelGGL(bwd_recompute_mfma_kernel<kCap>, grid, dim3(kThreads), 0, stream, c, s, map, tps);
-  else
-    hipLaunchKernelGGL(bwd_recompute_mfma_kernel<kNoCap>, grid, dim3(kThreads), 0, stream, c, s, map, tps);
+  if (s.tile_list) {
+    // one share of the work list per CU, at most one per tile
+    int groups = 256;
+    if (groups > n_tiles * v_tiles) groups = (n_tiles * v_tiles + kXcds - 1) / kXcds * kXcds;
+    dim3 grid(groups);
+    if (c.softcap > 0.f)
+      hipLaunchKernelGGL((bwd_recompute_mfma_kernel<kCap, true>), grid, dim3(kThreads), 0, stream, c, s, map, tps);
+    else
+      hipLaunchKernelGGL((bwd_recompute_mfma_kernel<kNoCap, true>), grid, dim3(kThreads), 0, stream, c, s, map, tps);
+  } else {
+    dim3 grid(xcd_map_grid(map));
+    if (c.softcap > 0.f)
+      hipLaunchKernelGGL((bwd_recompute_mfma_kernel<kCap, false>), grid, dim3(kThreads), 0, stream, c, s, map, tps);
+    else
+      hipLaunchKernelGGL((bwd_recompute_mfma_kernel<kNoCap, false>), grid, dim3(kThreads), 0, stream, c, s, map, tps);
+  }
   hipLaunchKernelGGL(count_flags_kernel, dim3(8), dim3(256), 0, stream, s.flags_nv, n_tiles,
                      s.vs / 64, s.v0, c.V, c.stats);
   return hipGetLastError();

@@ -120,11 +120,15 @@ bool use_mfma(int64_t D, const cce_opts* o) {
   return o->dtype == CCE_BF16 && !(o->flags & CCE_PLAIN_KERNELS) && D % 64 == 0;
 }
 
+size_t block_max_bytes(int64_t N, int64_t V) {
+  return (size_t)((V + 127) / 128) * (size_t)round_up(N, 256) * sizeof(uint16_t);
+}
+
 int check_common(const void* E, const void* C, const int64_t* targets, int64_t N, int64_t D, int64_t V,
                  float softcap, const cce_opts* o) {
   if (!o) return CCE_EINVAL;
   if (o->dtype != CCE_BF16 && o->dtype != CCE_F32) return CCE_EUNSUPPORTED;
-  if (o->flags & ~(uint32_t)(CCE_FILTER_DE | CCE_FILTER_DC | CCE_VOCAB_SORT | CCE_PLAIN_KERNELS)) return CCE_EUNSUPPORTED;
+  if (o->flags & ~(uint32_t)(CCE_FILTER_DE | CCE_FILTER_DC | CCE_VOCAB_SORT | CCE_PLAIN_KERNELS | CCE_SKIP_TILES)) return CCE_EUNSUPPORTED;
   if (!E || !C || !targets) return CCE_EINVAL;
   if (N <= 0 || D <= 0 || V <= 0) return CCE_EINVAL;
   if (N > (int64_t)0x7fff0000 || V > (int64_t)0x7fff0000 || D > (1 << 22)) return CCE_EINVAL;
@@ -132,6 +136,10 @@ int check_common(const void* E, const void* C, const int64_t* targets, int64_t N
   if (!(o->filter_eps >= 0.f) || !(o->filter_eps < 1.f)) return CCE_EINVAL;
   if (!aligned(E, 16) || !aligned(C, 16) || !aligned(targets, 8)) return CCE_EINVAL;
   if (o->workspace && !aligned(o->workspace, 256)) return CCE_EINVAL;
+  if ((o->flags & CCE_SKIP_TILES) && o->block_max) {
+    if (!aligned(o->block_max, 256)) return CCE_EINVAL;
+    if (o->block_max_bytes < block_max_bytes(N, V)) return CCE_EWORKSPACE;
+  }
   return CCE_OK;
 }
 
@@ -174,10 +182,12 @@ struct BwdPlan {
   size_t off_partial, off_mean, off_key, off_key_sorted, off_index, off_perm, off_inverse, off_targets, off_Cs[kSlabBuffers],
       off_sort_temp;
   size_t sort_temp_bytes;
+  // work lists of the recompute kernel (CCE_SKIP_TILES)
+  size_t off_tile_flag, off_tile_list, off_tile_count;
   size_t total_bytes;
 };
 
-BwdPlan layout_backward(bool mfma, int64_t N, int64_t D, int64_t V, int64_t vs, bool sort) {
+BwdPlan layout_backward(bool mfma, int64_t N, int64_t D, int64_t V, int64_t vs, bool sort, bool lists) {
   BwdPlan p{};
   p.mfma = mfma;
   p.vs = vs;
@@ -205,6 +215,13 @@ BwdPlan layout_backward(bool mfma, int64_t N, int64_t D, int64_t V, int64_t vs, 
       p.sort_temp_bytes = vocab_sort_temp_bytes(V);
       p.off_sort_temp = off; off += align_up(p.sort_temp_bytes, 256);
     }
+    if (lists) {
+      const size_t n_tiles = (size_t)(p.Np / 256), v_tiles = (size_t)((V + 255) / 256), slab_tiles = (size_t)(vs / 256);
+      const size_t slabs = (v_tiles + slab_tiles - 1) / slab_tiles;
+      p.off_tile_flag = off;  off += align_up(n_tiles * v_tiles, 256);
+      p.off_tile_list = off;  off += align_up(slabs * n_tiles * slab_tiles * 4, 256);
+      p.off_tile_count = off; off += align_up(slabs * 4, 256);
+    }
   } else {
     p.Np = N;
     p.off_flags[0] = off;
@@ -228,7 +245,7 @@ int64_t recommended_slab(bool mfma, int64_t V) {
 }
 
 // widest slab (multiple of the tile width, at most the recommended one) that fits `bytes`
-int64_t fit_slab(bool mfma, int64_t N, int64_t D, int64_t V, size_t bytes, bool sort) {
+int64_t fit_slab(bool mfma, int64_t N, int64_t D, int64_t V, size_t bytes, bool sort, bool lists) {
   const int64_t t = slab_tile(mfma);
   int64_t lo = 0, hi = recommended_slab(mfma, V) / t;   // in tiles
   if (mfma) {
@@ -238,7 +255,7 @@ int64_t fit_slab(bool mfma, int64_t N, int64_t D, int64_t V, size_t bytes, bool 
   }
   while (lo < hi) {
     int64_t mid = (lo + hi + 1) / 2;
-    if (layout_backward(mfma, N, D, V, mid * t, sort).total_bytes <= bytes) lo = mid; else hi = mid - 1;
+    if (layout_backward(mfma, N, D, V, mid * t, sort, lists).total_bytes <= bytes) lo = mid; else hi = mid - 1;
   }
   return lo * t;
 }
@@ -274,12 +291,18 @@ size_t cce_workspace_bytes(int op, int64_t N, int64_t D, int64_t V, const cce_op
   if (opts->dtype != CCE_BF16 && opts->dtype != CCE_F32) return 0;
   const bool mfma = use_mfma(D, opts);
   const bool sort = mfma && (opts->flags & CCE_VOCAB_SORT);
+  const bool lists = mfma && !sort && (opts->flags & CCE_SKIP_TILES);
   switch (op) {
     case CCE_OP_FORWARD: return plan_forward(N, D, V, opts).total_bytes;
-    case CCE_OP_BACKWARD: return layout_backward(mfma, N, D, V, recommended_slab(mfma, V), sort).total_bytes;
-    case CCE_OP_BACKWARD_MIN: return layout_backward(mfma, N, D, V, slab_tile(mfma), sort).total_bytes;
+    case CCE_OP_BACKWARD: return layout_backward(mfma, N, D, V, recommended_slab(mfma, V), sort, lists).total_bytes;
+    case CCE_OP_BACKWARD_MIN: return layout_backward(mfma, N, D, V, slab_tile(mfma), sort, lists).total_bytes;
     default: return 0;
   }
+}
+
+size_t cce_block_max_bytes(int64_t N, int64_t V) {
+  if (N <= 0 || V <= 0) return 0;
+  return block_max_bytes(N, V);
 }
 
 void cce_filter_block(int64_t N, int64_t D, int64_t V, const cce_opts* opts, int* block_rows, int* block_cols) {
@@ -312,6 +335,10 @@ int cce_forward_ex(const void* E, const void* C, const int64_t* targets, int64_t
     p.n_tiles = plan.n_tiles; p.v_tiles = plan.v_tiles;
     p.splits = plan.splits; p.tiles_per_split = plan.tiles_per_split;
     p.map = make_xcd_map(plan.n_tiles, plan.splits);
+    if ((opts->flags & CCE_SKIP_TILES) && opts->block_max) {
+      p.block_max = (uint16_t*)opts->block_max;
+      p.block_max_stride = (int)round_up(N, 256);
+    }
     CCE_HIP(launch_fwd_lse_mfma(p, stream));
   } else {
     FwdPlainParams p{};
@@ -343,9 +370,12 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
   const bool sort = (opts->flags & CCE_VOCAB_SORT) != 0;
   if (sort && !mfma) return CCE_EUNSUPPORTED;   // vocabulary sorting exists on the bf16 MFMA path only
   if (!opts->workspace) return CCE_EWORKSPACE;
-  const int64_t vs = fit_slab(mfma, N, D, V, opts->workspace_bytes, sort);
+  // the workspace is laid out for work lists whenever the flag asks for them (as sized by
+  // cce_workspace_bytes); they are used only when nothing but filtered products reads GZ
+  const bool lists_layout = mfma && !sort && (opts->flags & CCE_SKIP_TILES);
+  const int64_t vs = fit_slab(mfma, N, D, V, opts->workspace_bytes, sort, lists_layout);
   if (vs <= 0) return CCE_EWORKSPACE;
-  const BwdPlan plan = layout_backward(mfma, N, D, V, vs, sort);
+  const BwdPlan plan = layout_backward(mfma, N, D, V, vs, sort, lists_layout);
   hipStream_t stream = (hipStream_t)opts->stream;
   char* ws = (char*)opts->workspace;
 
@@ -392,6 +422,23 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
       c.targets = v.targets_sorted;    // from here on the vocabulary is indexed by sorted position
       s.perm = v.perm;
     }
+    const bool use_lists = lists_layout && opts->block_max && c.filter_dE && c.filter_dC && c.eps > 0.f;
+    const int64_t slab_tiles = vs / 256;
+    if (use_lists) {
+      TileListParams t{};
+      t.block_max = (const uint16_t*)opts->block_max;
+      t.stride = (int)plan.Np;
+      t.targets = targets; t.lse = lse;
+      t.N = (int)N; t.V = (int)V; t.ignore_index = ignore_index;
+      t.log_eps = logf(c.eps) - 0.02f;   // margin for the fp32 rounding of lse and of the recorded maxima
+      t.n_tiles = (int)(plan.Np / 256); t.v_tiles = (int)((V + 255) / 256);
+      t.slab_tiles = (int)slab_tiles;
+      t.slabs = (int)((t.v_tiles + slab_tiles - 1) / slab_tiles);
+      t.tile_flag = (uint8_t*)(ws + plan.off_tile_flag);
+      t.tile_list = (uint32_t*)(ws + plan.off_tile_list);
+      t.tile_count = (uint32_t*)(ws + plan.off_tile_count);
+      CCE_HIP(launch_tile_lists(t, stream));
+    }
     int64_t slab = 0;
     for (int64_t v0 = 0; v0 < V; v0 += vs, ++slab) {
       const int b = (int)(slab % kSlabBuffers), e = (int)(slab % kEventRing);
@@ -410,6 +457,10 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
       }
       const int64_t rows_valid = (V - v0 < vs_this) ? V - v0 : vs_this;
       s.Crows = (const bf16*)C + v0 * D;
+      if (use_lists) {
+        s.tile_list = (const uint32_t*)(ws + plan.off_tile_list) + slab * (plan.Np / 256) * slab_tiles;
+        s.tile_count = (const uint32_t*)(ws + plan.off_tile_count) + slab;
+      }
       if (sort) {
         // the slab's rows of C, gathered in sorted order (its buffer was last read by the
         // recompute and the dE product of the slab that used it before, both waited for above)

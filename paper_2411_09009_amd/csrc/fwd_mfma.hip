@@ -24,14 +24,17 @@ enum { kNoCap = 0, kCapFixed = 1, kCapMax = 2 };
 // Fold one finished logit tile (this lane's 4 x 2 blocks) into the running base-2
 // statistics m2 = max(a)*log2e and s = sum 2^(a*log2e - m2) of the lane's two token
 // columns, and clear the accumulators.  RAGGED masks vocabulary rows >= V.
-template <int MODE, bool RAGGED>
+// REC additionally returns, per token column, the largest logit of the tile in base-2 units
+// (a * log2(e)) over this lane's rows, for the block-maximum record.
+template <int MODE, bool RAGGED, bool REC>
 __device__ inline void fold_tile(f32x16 (&acc)[kRB][kCB], float (&m2)[kCB], float (&s)[kCB], int lane,
-                                 int v_base, int V, float cap_scale, float cap_l2) {
+                                 int v_base, int V, float cap_scale, float cap_l2, float (&amax2)[kCB]) {
 #pragma unroll
   for (int cb = 0; cb < kCB; ++cb) {
     if (MODE == kCapFixed) {
       // a*log2e - cap*log2e = -2*cap_l2 / (1 + 2^(z*cap_scale))
       float sum = 0.f;
+      float rmin = INFINITY;   // REC: the largest logit has the smallest r = 1 / (1 + 2^(z * cap_scale))
 #pragma unroll
       for (int rb = 0; rb < kRB; ++rb)
 #pragma unroll
@@ -39,12 +42,17 @@ __device__ inline void fold_tile(f32x16 (&acc)[kRB][kCB], float (&m2)[kCB], floa
           float e = __builtin_amdgcn_exp2f(acc[rb][cb][i] * cap_scale);
           float r = __builtin_amdgcn_rcpf(1.f + e);
           float t = __builtin_amdgcn_exp2f(-2.f * cap_l2 * r);
-          if (RAGGED && v_base + rb * 32 + acc_row(lane, i) >= V) t = 0.f;
+          if (RAGGED && v_base + rb * 32 + acc_row(lane, i) >= V) {
+            t = 0.f;
+            r = INFINITY;
+          }
+          if (REC) rmin = fminf(rmin, r);
           sum += t;
           acc[rb][cb][i] = 0.f;
         }
       s[cb] += sum;
       m2[cb] = cap_l2;
+      if (REC) amax2[cb] = rmin == INFINITY ? -INFINITY : fmaf(-2.f * cap_l2, rmin, cap_l2);
     } else if (MODE == kNoCap) {
       float tmax = -INFINITY;
 #pragma unroll
@@ -54,6 +62,7 @@ __device__ inline void fold_tile(f32x16 (&acc)[kRB][kCB], float (&m2)[kCB], floa
           if (RAGGED && v_base + rb * 32 + acc_row(lane, i) >= V) acc[rb][cb][i] = -INFINITY;
           tmax = fmaxf(tmax, acc[rb][cb][i]);
         }
+      if (REC) amax2[cb] = tmax * kLog2e;
       const float m_new = fmaxf(m2[cb], tmax * kLog2e);
       // a lane whose rows are all masked so far has m_new = -inf: subtract 0 instead, every
       // term is then 2^(-inf) = 0 and no inf - inf arises
@@ -81,6 +90,7 @@ __device__ inline void fold_tile(f32x16 (&acc)[kRB][kCB], float (&m2)[kCB], floa
           acc[rb][cb][i] = a2;
           tmax = fmaxf(tmax, a2);
         }
+      if (REC) amax2[cb] = tmax;
       const float m_new = fmaxf(m2[cb], tmax);
       const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
       float sum = 0.f;
@@ -97,7 +107,14 @@ __device__ inline void fold_tile(f32x16 (&acc)[kRB][kCB], float (&m2)[kCB], floa
   }
 }
 
-template <int MODE, bool SORT>
+// bf16 bit pattern of x rounded towards +infinity (never below x)
+__device__ inline uint16_t bf16_round_up(float x) {
+  const uint32_t u = __float_as_uint(x);
+  if ((u & 0x7f800000u) == 0x7f800000u) return (uint16_t)(u >> 16);     // inf / nan: keep
+  return (uint16_t)((x >= 0.f ? u + 0xffffu : u) >> 16);                  // negative: truncation moves up
+}
+
+template <int MODE, bool REC>
 __global__ __launch_bounds__(kThreads) void fwd_lse_mfma_kernel(FwdMfmaParams p) {
   __shared__ __attribute__((aligned(1024))) char lds[kLdsBytes];
 
@@ -134,13 +151,28 @@ __global__ __launch_bounds__(kThreads) void fwd_lse_mfma_kernel(FwdMfmaParams p)
   const float cap_scale = MODE != kNoCap ? 2.f * kLog2e / p.softcap : 0.f;   // exp(2z/cap) = 2^(z*cap_scale)
   const float cap_l2 = MODE != kNoCap ? p.softcap * kLog2e : kLog2e;
 
-  sweep_tiles(tc, lds, (const char*)p.C, p.V, ld_bytes, vt0, vt1, gQ, offQ, KT, acc, [&](int vt) {
+  sweep_tiles<REC ? 2 : 0>(tc, lds, (const char*)p.C, p.V, ld_bytes, vt0, vt1, gQ, offQ, KT, acc, [&](int vt) {
     // fold the finished logit tile into the running (max, sum)
     const int v_base = vt * kTileR + tc.wave_r * kWaveRows;
+    float amax2[kCB] = {-INFINITY, -INFINITY};
     if ((vt + 1) * kTileR > p.V)
-      fold_tile<MODE, true>(acc, m2, s, tc.lane, v_base, p.V, cap_scale, cap_l2);
+      fold_tile<MODE, true, REC>(acc, m2, s, tc.lane, v_base, p.V, cap_scale, cap_l2, amax2);
     else
-      fold_tile<MODE, false>(acc, m2, s, tc.lane, v_base, p.V, cap_scale, cap_l2);
+      fold_tile<MODE, false, REC>(acc, m2, s, tc.lane, v_base, p.V, cap_scale, cap_l2, amax2);
+    if (REC && v_base < p.V) {
+      // this wave's 128 vocabulary rows are one block of the record: merge the two lane halves
+      // and store one value per token (natural-log units, rounded up to bf16); 32-bit element
+      // offsets keep the address in one register
+      const uint32_t row = (uint32_t)(v_base / kWaveRows) * (uint32_t)p.block_max_stride +
+                           (uint32_t)(n0 + tc.wave_c * kWaveCols + (tc.lane & 31));
+#pragma unroll
+      for (int cb = 0; cb < kCB; ++cb) {
+        const float a = fmaxf(amax2[cb], __shfl_xor(amax2[cb], 32)) * kLn2;
+        if (tc.lane < 32) p.block_max[row + (uint32_t)(cb * 32)] = bf16_round_up(a);
+      }
+      return true;    // two stores, the last vector-memory operations issued
+    }
+    return false;
   });
 
   // ---- merge the two lane halves, then the two row-waves, and write the partial ----
@@ -172,12 +204,18 @@ __global__ __launch_bounds__(kThreads) void fwd_lse_mfma_kernel(FwdMfmaParams p)
 
 hipError_t launch_fwd_lse_mfma(const FwdMfmaParams& p, hipStream_t stream) {
   dim3 grid(xcd_map_grid(p.map)), block(kThreads);
-  if (p.softcap > 40.f)
-    hipLaunchKernelGGL((fwd_lse_mfma_kernel<kCapMax, false>), grid, block, 0, stream, p);
-  else if (p.softcap > 0.f)
-    hipLaunchKernelGGL((fwd_lse_mfma_kernel<kCapFixed, false>), grid, block, 0, stream, p);
-  else
-    hipLaunchKernelGGL((fwd_lse_mfma_kernel<kNoCap, false>), grid, block, 0, stream, p);
+  const int mode = p.softcap > 40.f ? kCapMax : p.softcap > 0.f ? kCapFixed : kNoCap;
+#define CCE_LAUNCH_FWD(M, R) hipLaunchKernelGGL((fwd_lse_mfma_kernel<M, R>), grid, block, 0, stream, p)
+  if (p.block_max) {
+    if (mode == kCapMax) CCE_LAUNCH_FWD(kCapMax, true);
+    else if (mode == kCapFixed) CCE_LAUNCH_FWD(kCapFixed, true);
+    else CCE_LAUNCH_FWD(kNoCap, true);
+  } else {
+    if (mode == kCapMax) CCE_LAUNCH_FWD(kCapMax, false);
+    else if (mode == kCapFixed) CCE_LAUNCH_FWD(kCapFixed, false);
+    else CCE_LAUNCH_FWD(kNoCap, false);
+  }
+#undef CCE_LAUNCH_FWD
   return hipGetLastError();
 }
 

@@ -59,6 +59,9 @@ struct FwdMfmaParams {
   int n_tiles, v_tiles; // ceil(N / 256), ceil(V / 256)
   int splits, tiles_per_split;
   XcdMap map;              // a = token tile, b = vocabulary split
+  uint16_t* block_max;     // optional [ceil(V / 128), block_max_stride] bf16 bits: for every token the largest
+                           // (soft-capped) logit within each 128-wide vocabulary block, rounded up; nullptr = off
+  int block_max_stride;    // N rounded up to 256
 };
 hipError_t launch_fwd_lse_mfma(const FwdMfmaParams& p, hipStream_t stream);
 
@@ -127,7 +130,29 @@ struct BwdMfmaSlab {
                         // gathered copy when the vocabulary is walked in sorted order
   const int* perm;      // sorted position -> original vocabulary index (rows of dC are written
                         // through it); nullptr = identity
+  // optional work list of the recompute kernel (nullptr = every tile of the slab):
+  // tile_list[i] = token tile << 16 | slab-local vocabulary tile, token-tile major; *tile_count entries
+  const uint32_t* tile_list;
+  const uint32_t* tile_count;
 };
+
+// ---- tiles the gradient filter cannot skip (from the forward's block-maximum record) ----
+struct TileListParams {
+  const uint16_t* block_max;   // [ceil(V / 128), stride] bf16 bits, see FwdMfmaParams
+  int stride;
+  const int64_t* targets;
+  const float* lse;
+  int N, V;
+  int64_t ignore_index;
+  float log_eps;               // log(filter_eps) minus a rounding margin
+  int n_tiles, v_tiles;        // ceil(N / 256), ceil(V / 256)
+  int slab_tiles;              // vocabulary tiles per slab
+  int slabs;
+  uint8_t* tile_flag;          // [n_tiles, v_tiles] scratch
+  uint32_t* tile_list;         // [slabs, n_tiles * slab_tiles] out
+  uint32_t* tile_count;        // [slabs] out
+};
+hipError_t launch_tile_lists(const TileListParams& p, hipStream_t stream);
 hipError_t launch_bwd_recompute_mfma(const BwdCommon& c, const BwdMfmaSlab& s, hipStream_t stream);
 hipError_t launch_bwd_dE_mfma(const BwdCommon& c, const BwdMfmaSlab& s, hipStream_t stream);
 hipError_t launch_bwd_dC_mfma(const BwdCommon& c, const BwdMfmaSlab& s, void* out_dC, hipStream_t stream);

@@ -92,6 +92,11 @@ __device__ inline void lds_wait(bf16x8 (&p)[kRB], bf16x8 (&q)[kCB]) {
 }
 
 __device__ inline void wait_dma() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// Wait until at most N vector-memory operations of this wave are outstanding.  They retire in
+// issue order, so everything issued before the last N (the direct loads of the coming stage)
+// has landed while the N most recent ones (an epilogue's stores) may still be in flight.
+template <int N>
+__device__ inline void wait_dma_except() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
 struct TileCoords {
   int lane, wave, wave_r, wave_c;
@@ -240,7 +245,9 @@ __device__ inline void pin_acc(f32x16 (&acc)[kRB][kCB]) {
 //   next(src)      fills the DMA source of the following stage; it is called once per
 //                  stage, in stage order (a cursor that runs two stages ahead of the MFMAs).
 //   step_done(i)   is called after the MFMAs of stage i have been issued; an epilogue that
-//                  consumes the accumulators goes here (and must leave them zeroed).
+//                  consumes the accumulators goes here (and must leave them zeroed).  It returns
+//                  true when it has just issued at least KSTORE global stores as its last
+//                  vector-memory operations: the next stage then does not wait for them.
 //
 // Per stage i the wave runs four 16-deep MFMA groups.  Fragments are double-buffered in
 // registers: the reads for group g+1 are in flight while group g multiplies.  The single
@@ -251,7 +258,7 @@ __device__ inline void pin_acc(f32x16 (&acc)[kRB][kCB]) {
 // that their address-queue back-pressure never delays an MFMA.  Each load has one full
 // stage to arrive.
 // PK / QK: the P / Q operand is K-major (see the top of this file).
-template <bool PK = false, bool QK = false, class Next, class StepDone>
+template <bool PK = false, bool QK = false, int KSTORE = 0, class Next, class StepDone>
 __device__ inline void mma_pipeline(const TileCoords& tc, char* lds, int nsteps, f32x16 (&acc)[kRB][kCB], Next next,
                                     StepDone step_done) {
   if (nsteps <= 0) return;
@@ -267,7 +274,8 @@ __device__ inline void mma_pipeline(const TileCoords& tc, char* lds, int nsteps,
   CCE_READ_FRAGS(0, lds_base, 0)
   lds_wait(p[0], q[0]);
   int stage = 0;
-  // The loop body is branch free: the last two iterations fetch a stage nobody multiplies
+  bool stores_pending = false;
+  // The loop body is branch free (but for the choice of wait below): the last two iterations fetch a stage nobody multiplies
   // (next() keeps returning an in-bounds source) and prefetch fragments nobody uses.
   for (int i = 0; i < nsteps; ++i) {
     const uint32_t cur = lds_base + stage * kStageBytes;
@@ -284,7 +292,8 @@ __device__ inline void mma_pipeline(const TileCoords& tc, char* lds, int nsteps,
     CCE_MMA8(0)
     __builtin_amdgcn_sched_barrier(0);
     lds_wait(p[1], q[1]);
-    wait_dma();
+    if (KSTORE > 0 && stores_pending) wait_dma_except<KSTORE>();
+    else wait_dma();
     __builtin_amdgcn_s_barrier();
     CCE_READ_FRAGS(0, oth, 0)
     next(src);
@@ -301,7 +310,7 @@ __device__ inline void mma_pipeline(const TileCoords& tc, char* lds, int nsteps,
         __builtin_amdgcn_sched_barrier(0);
       }
     lds_wait(p[0], q[0]);
-    step_done(i);
+    stores_pending = step_done(i);
     stage ^= 1;
   }
   wait_dma();   // the surplus loads must have landed before the LDS is reused or released
@@ -310,8 +319,8 @@ __device__ inline void mma_pipeline(const TileCoords& tc, char* lds, int nsteps,
 // Sweep P tiles t0 .. t1-1 (tile t = rows [256 t, 256 t + 256) of P, clamped to p_rows)
 // against one fixed 256-row Q tile, with the K loop running seamlessly from one tile into
 // the next.  After the last stage of each tile, on_tile(t) consumes the accumulators and
-// must leave them zeroed.
-template <class OnTile>
+// must leave them zeroed; its return value is that of mma_pipeline's step_done.
+template <int KSTORE = 0, class OnTile>
 __device__ inline void sweep_tiles(const TileCoords& tc, char* lds, const char* P, int p_rows, int64_t ld_bytes,
                                    int t0, int t1, const char* gQ, const uint32_t (&offQ)[4], int KT,
                                    f32x16 (&acc)[kRB][kCB], OnTile on_tile) {
@@ -322,7 +331,7 @@ __device__ inline void sweep_tiles(const TileCoords& tc, char* lds, const char* 
   uint32_t offP[4];
   dma_offsets(tc, min(kTileR, p_rows - t0 * kTileR), ld_bytes, offP);
   int kt = 0, t = t0;   // compute cursor
-  mma_pipeline(
+  mma_pipeline<false, false, KSTORE>(
       tc, lds, (t1 - t0) * KT, acc,
       [&](StageSrc& src) {
         const int64_t koff = (int64_t)cur_kt * (kTileK * 2);
@@ -344,9 +353,53 @@ __device__ inline void sweep_tiles(const TileCoords& tc, char* lds, const char* 
       [&](int) {
         if (++kt == KT) {
           kt = 0;
-          on_tile(t);
+          const bool stored = on_tile(t);
           ++t;
+          return stored;
         }
+        return false;
+      });
+}
+
+// Sweep entries e0 .. e1-1 of a list of independent 256 x 256 tiles, the K loop running
+// seamlessly from one tile into the next.  src_of(e, gP, offP, gQ, offQ) fills the operand
+// sources of entry e at K offset 0 (both operands K-contiguous); on_tile(e) consumes the
+// accumulators after the entry's last stage and must leave them zeroed (return value as above).
+template <int KSTORE = 0, class SrcOf, class OnTile>
+__device__ inline void sweep_entries(const TileCoords& tc, char* lds, int e0, int e1, int KT, f32x16 (&acc)[kRB][kCB],
+                                     SrcOf src_of, OnTile on_tile) {
+  if (e0 >= e1) return;
+  int cur_e = e0, cur_kt = 0;   // DMA cursor
+  const char *gP, *gQ;
+  uint32_t offP[4], offQ[4];
+  src_of(cur_e, gP, offP, gQ, offQ);
+  int kt = 0, e = e0;           // compute cursor
+  mma_pipeline<false, false, KSTORE>(
+      tc, lds, (e1 - e0) * KT, acc,
+      [&](StageSrc& src) {
+        const int64_t koff = (int64_t)cur_kt * (kTileK * 2);
+        src.gP = gP + koff;
+        src.gQ = gQ + koff;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { src.offP[j] = offP[j]; src.offQ[j] = offQ[j]; }
+        if (++cur_kt == KT) {
+          if (cur_e + 1 < e1) {
+            cur_kt = 0;
+            ++cur_e;
+            src_of(cur_e, gP, offP, gQ, offQ);
+          } else {
+            cur_kt = KT - 1;   // past the end: keep re-fetching the last slice (surplus loads)
+          }
+        }
+      },
+      [&](int) {
+        if (++kt == KT) {
+          kt = 0;
+          const bool stored = on_tile(e);
+          ++e;
+          return stored;
+        }
+        return false;
       });
 }
 

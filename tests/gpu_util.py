@@ -26,23 +26,23 @@ def workspace(nbytes):
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device="cuda:0")
 
 
-def run_forward(w, E, C, t, flags=None, softcap=None):
+def run_forward(w, E, C, t, flags=None, softcap=None, block_max=None):
     cap = w.softcap if softcap is None else softcap
     o = L.make_opts(dtype_code(w), flags=flags)
     ws = workspace(L.cce_workspace_bytes(L.CCE_OP_FORWARD, w.N, w.D, w.V, o))
-    o = L.make_opts(dtype_code(w), flags=flags, workspace=ws)
+    o = L.make_opts(dtype_code(w), flags=flags, workspace=ws, block_max=block_max)
     loss, lse = L.cce_forward_ex(E, C, t, cap, w.ignore_index, o)
     torch.cuda.synchronize()
     return loss, lse
 
 
-def run_backward(w, E, C, t, lse, dloss, flags=None, eps=None, ws_bytes=None, softcap=None, op=None):
+def run_backward(w, E, C, t, lse, dloss, flags=None, eps=None, ws_bytes=None, softcap=None, op=None, block_max=None):
     cap = w.softcap if softcap is None else softcap
     o = L.make_opts(dtype_code(w), flags=flags, filter_eps=eps)
     if ws_bytes is None:
         ws_bytes = L.cce_workspace_bytes(L.CCE_OP_BACKWARD if op is None else op, w.N, w.D, w.V, o)
     ws = workspace(ws_bytes)
-    o = L.make_opts(dtype_code(w), flags=flags, filter_eps=eps, workspace=ws)
+    o = L.make_opts(dtype_code(w), flags=flags, filter_eps=eps, workspace=ws, block_max=block_max)
     dE, dC = L.cce_backward_ex(E, C, t, lse, dloss, cap, w.ignore_index, o)
     torch.cuda.synchronize()
     stats = L.cce_backward_filter_stats(ws)

@@ -99,3 +99,11 @@ def test_full_size_matches_stored_oracle(cce, name):
           flush=True)
     assert sE <= elemE + eE + 1e-3 and sC <= elemC + eC + 1e-3
     assert stats_s[0] == stats_f[0] and 0 < stats_s[1] <= stats_s[0]
+
+    print("backward (filtered, tiles skipped from the forward's block maxima) %s" % name, flush=True)
+    both = L.CCE_FILTER_DE | L.CCE_FILTER_DC
+    bm = torch.empty(L.cce_block_max_bytes(w.N, w.V), dtype=torch.uint8, device="cuda")
+    loss2, lse2 = run_forward(w, E, C, t, flags=both | L.CCE_SKIP_TILES, block_max=bm)
+    assert torch.equal(lse2, lse) and torch.equal(loss2, loss)
+    dEk, dCk, stats_k = run_backward(w, E, C, t, lse, dloss, flags=both | L.CCE_SKIP_TILES, block_max=bm)
+    assert torch.equal(dEk, dEf) and torch.equal(dCk, dCf) and stats_k == stats_f

@@ -141,6 +141,45 @@ def test_vocabulary_sorting_changes_the_order_not_the_result(cce, name, N, D, V,
     assert ei.value.status == -3
 
 
+@pytest.mark.parametrize("name,N,D,V,kw", [MID[0], ("gemma2_2b", 1100, 128, 9000, {}), ("small_vocab", 520, 64, 4100, {}),
+                                           ("stress_peaked", 700, 128, 5000, {})])
+def test_skipping_tiles_the_filter_drops_changes_nothing(cce, name, N, D, V, kw):
+    """CCE_SKIP_TILES: tiles whose recorded logit maxima rule out any entry >= eps are not recomputed."""
+    w = make(name, N=N, D=D, V=V, **kw)
+    E, C, t = to_device(w)
+    both = L.CCE_FILTER_DE | L.CCE_FILTER_DC
+    bm = torch.full((L.cce_block_max_bytes(w.N, w.V),), 0x7f, dtype=torch.uint8, device="cuda")   # poison: large positive
+    loss0, lse0 = run_forward(w, E, C, t)
+    loss1, lse1 = run_forward(w, E, C, t, flags=both | L.CCE_SKIP_TILES, block_max=bm)
+    assert torch.equal(loss0, loss1) and torch.equal(lse0, lse1)     # recording does not touch the result
+    # the record is an upper bound, within bf16 rounding, of the oracle's block maxima
+    A = O.logits(w.E64(), w.C64(), w.softcap)
+    nb = (w.V + 127) // 128
+    stride = (w.N + 255) // 256 * 256
+    rec = bm.view(torch.int16).view(nb, stride)[:, :w.N].to(torch.int32).cpu().numpy().astype(np.uint32) << 16
+    rec = rec.view(np.float32).astype(np.float64).T                   # [N, nb]
+    ref = np.stack([A[:, b * 128:(b + 1) * 128].max(axis=1) for b in range(nb)], axis=1)
+    assert np.all(rec >= ref - 1e-3) and np.all(rec <= ref + np.abs(ref) * 2.0 ** -7 + 2e-3)
+    dloss = torch.from_numpy(w.mean_dloss()).cuda()
+    dE0, dC0, st0 = run_backward(w, E, C, t, lse0, dloss)
+    dE1, dC1, st1 = run_backward(w, E, C, t, lse0, dloss, flags=both | L.CCE_SKIP_TILES, block_max=bm)
+    print("skip tiles %s: blocks kept %d / %d" % (name, st1[1], st1[0]))
+    assert torch.equal(dE0, dE1) and torch.equal(dC0, dC1) and st0 == st1
+    # narrow slabs, and filter off for one product (the lists must then not be used)
+    dE2, dC2, _ = run_backward(w, E, C, t, lse0, dloss, flags=both | L.CCE_SKIP_TILES, block_max=bm,
+                               op=L.CCE_OP_BACKWARD_MIN)
+    dE2r, dC2r, _ = run_backward(w, E, C, t, lse0, dloss, op=L.CCE_OP_BACKWARD_MIN)
+    assert torch.equal(dE2r, dE2) and torch.equal(dC2r, dC2)
+    dE3, dC3, _ = run_backward(w, E, C, t, lse0, dloss, flags=L.CCE_FILTER_DE)
+    dE4, dC4, _ = run_backward(w, E, C, t, lse0, dloss, flags=L.CCE_FILTER_DE | L.CCE_SKIP_TILES, block_max=bm)
+    assert torch.equal(dE3, dE4) and torch.equal(dC3, dC4)
+    # an undersized record is refused
+    o = L.make_opts(L.CCE_BF16, flags=both | L.CCE_SKIP_TILES, workspace=workspace(1 << 24), block_max=bm[:256])
+    with pytest.raises(L.CceError) as ei:
+        L.cce_forward_ex(E, C, t, w.softcap, w.ignore_index, o)
+    assert ei.value.status == -2
+
+
 def test_tiny_config_fp32_full_parity(cce):
     """Config 1 (N=256, D=64, V=1024, fp32, 5% ignored): the oracle covers every output."""
     w = make("tiny")
