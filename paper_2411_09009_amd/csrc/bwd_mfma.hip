@@ -100,9 +100,8 @@ __global__ __launch_bounds__(kThreads) void bwd_recompute_mfma_kernel(BwdCommon 
     const int groups = (int)gridDim.x, per_xcd = groups / kXcds;
     const int logical = ((int)blockIdx.x % kXcds) * per_xcd + (int)blockIdx.x / kXcds;
     const int count = (int)*sl.tile_count;
-    const int share = (count + groups - 1) / groups;
-    e0 = logical * share;
-    e1 = min(e0 + share, count);
+    e0 = (int)((int64_t)logical * count / groups);        // shares differ by at most one entry
+    e1 = (int)((int64_t)(logical + 1) * count / groups);
     if (e0 >= e1) return;
     n_tile = (int)(sl.tile_list[e0] >> 16);
   } else {
@@ -395,11 +394,17 @@ __global__ __launch_bounds__(kThreads) void bwd_product_mfma_kernel(BwdCommon c,
   }
 }
 
-// counts the (256 token x 64 vocabulary) filter blocks of a slab and how many were kept
-__global__ void count_flags_kernel(const uint32_t* flags_nv, int n_tiles, int vsteps, int v0, int V,
-                                   FilterStats* stats) {
+// counts the (256 token x 64 vocabulary) filter blocks of every slab and how many were kept;
+// one workgroup per slab, whose flags start at flags + slab * region_words
+__global__ __launch_bounds__(256) void count_flags_kernel(const uint32_t* flags, int64_t region_words, int n_tiles,
+                                                          int vs, int V, FilterStats* stats) {
+  const int slab = blockIdx.x;
+  const int v0 = slab * vs;
+  const int vs_this = min(vs, (V - v0 + 255) / 256 * 256);
+  const int vsteps = vs_this / 64;
+  const uint32_t* flags_nv = flags + (int64_t)slab * region_words;
   unsigned long long total = 0, kept = 0;
-  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n_tiles * vsteps; i += gridDim.x * blockDim.x) {
+  for (int i = threadIdx.x; i < n_tiles * vsteps; i += blockDim.x) {
     int vstep = i % vsteps;
     if (v0 + vstep * 64 < V) {
       ++total;
@@ -431,11 +436,6 @@ hipError_t launch_tile_lists(const TileListParams& p, hipStream_t stream) {
 
 hipError_t launch_bwd_recompute_mfma(const BwdCommon& c, const BwdMfmaSlab& s, hipStream_t stream) {
   const int n_tiles = s.Np / kTileC, v_tiles = s.vs / kTileR;
-  // clear the slab's flags
-  const int64_t nflags = (int64_t)n_tiles * (s.vs / 64) + (int64_t)v_tiles * (s.Np / 64);
-  // flags_nv and flags_vn are laid out back to back by the dispatcher
-  hipLaunchKernelGGL(zero_u32_kernel, dim3((unsigned)((nflags + 255) / 256)), dim3(256), 0, stream,
-                     s.flags_nv, nflags);
   int splits = (256 + n_tiles - 1) / n_tiles;
   if (splits > v_tiles) splits = v_tiles;
   if (splits < 1) splits = 1;
@@ -458,8 +458,19 @@ hipError_t launch_bwd_recompute_mfma(const BwdCommon& c, const BwdMfmaSlab& s, h
     else
       hipLaunchKernelGGL((bwd_recompute_mfma_kernel<kNoCap, false>), grid, dim3(kThreads), 0, stream, c, s, map, tps);
   }
-  hipLaunchKernelGGL(count_flags_kernel, dim3(8), dim3(256), 0, stream, s.flags_nv, n_tiles,
-                     s.vs / 64, s.v0, c.V, c.stats);
+  return hipGetLastError();
+}
+
+hipError_t launch_zero_flags(uint32_t* flags, int64_t words, hipStream_t stream) {
+  int64_t blocks = (words + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(zero_u32_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, flags, words);
+  return hipGetLastError();
+}
+
+hipError_t launch_count_flags(const uint32_t* flags, int64_t region_words, int slabs, int n_tiles, int vs, int V,
+                              FilterStats* stats, hipStream_t stream) {
+  hipLaunchKernelGGL(count_flags_kernel, dim3(slabs), dim3(256), 0, stream, flags, region_words, n_tiles, vs, V, stats);
   return hipGetLastError();
 }
 

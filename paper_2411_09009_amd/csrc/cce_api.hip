@@ -177,7 +177,9 @@ FwdPlan plan_forward(int64_t N, int64_t D, int64_t V, const cce_opts* o) {
 struct BwdPlan {
   bool mfma;
   int64_t Np, vs;          // padded token count, slab width
-  size_t off_flags[kSlabBuffers], off_dEacc, off_GZ[kSlabBuffers];   // flags, GZ: one per slab in flight (MFMA path)
+  size_t off_flags[kSlabBuffers], off_dEacc, off_GZ[kSlabBuffers];   // GZ: one per slab in flight (MFMA path);
+                                                                       // flags: [0] only, one region per slab on the MFMA path
+  size_t flag_region_words;
   // vocabulary sorting (MFMA path only)
   size_t off_partial, off_mean, off_key, off_key_sorted, off_index, off_perm, off_inverse, off_targets, off_Cs[kSlabBuffers],
       off_sort_temp;
@@ -196,9 +198,13 @@ BwdPlan layout_backward(bool mfma, int64_t N, int64_t D, int64_t V, int64_t vs, 
     p.Np = round_up(N, 256);
     p.off_dEacc = off;
     off += align_up((size_t)N * D * 4, 256);
+    {
+      const size_t slabs = (size_t)((round_up(V, 256) + vs - 1) / vs);
+      p.flag_region_words = (size_t)(p.Np / 256) * (vs / 64) + (size_t)(vs / 256) * (p.Np / 64);
+      p.off_flags[0] = off;
+      off += align_up(slabs * p.flag_region_words * 4, 256);
+    }
     for (int b = 0; b < kSlabBuffers; ++b) {
-      p.off_flags[b] = off;
-      off += align_up(((size_t)(p.Np / 256) * (vs / 64) + (size_t)(vs / 256) * (p.Np / 64)) * 4, 256);
       p.off_GZ[b] = off;
       off += align_up((size_t)p.Np * vs * 2, 256);
     }
@@ -439,6 +445,9 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
       t.tile_count = (uint32_t*)(ws + plan.off_tile_count);
       CCE_HIP(launch_tile_lists(t, stream));
     }
+    const int64_t n_slabs = (round_up(V, 256) + vs - 1) / vs;
+    uint32_t* flags_all = (uint32_t*)(ws + plan.off_flags[0]);
+    CCE_HIP(launch_zero_flags(flags_all, n_slabs * (int64_t)plan.flag_region_words, stream));
     int64_t slab = 0;
     for (int64_t v0 = 0; v0 < V; v0 += vs, ++slab) {
       const int b = (int)(slab % kSlabBuffers), e = (int)(slab % kEventRing);
@@ -447,7 +456,7 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
       s.vs = (int)vs_this;
       s.first = v0 == 0;
       s.GZ = (bf16*)(ws + plan.off_GZ[b]);
-      s.flags_nv = (uint32_t*)(ws + plan.off_flags[b]);
+      s.flags_nv = flags_all + slab * (int64_t)plan.flag_region_words;
       s.flags_vn = s.flags_nv + (plan.Np / 256) * (vs_this / 64);
       if (slab >= kSlabBuffers) {
         // this slab's buffers were last read by the products of slab - kSlabBuffers
@@ -490,6 +499,8 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
     CCE_HIP(hipStreamWaitEvent(stream, h->dC_done[e_last], 0));
     if (slab >= 2) CCE_HIP(hipStreamWaitEvent(stream, h->dC_done[(int)((slab - 2) % kEventRing)], 0));
     CCE_HIP(hipStreamWaitEvent(stream, h->dE_done[e_last], 0));
+    CCE_HIP(launch_count_flags(flags_all, (int64_t)plan.flag_region_words, (int)n_slabs, (int)(plan.Np / 256), (int)vs,
+                               (int)V, c.stats, stream));
     CCE_HIP(launch_store_dE(dEacc, out_dE, opts->dtype, N * D, stream));
     return CCE_OK;
   } else {

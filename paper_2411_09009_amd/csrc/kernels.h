@@ -123,8 +123,7 @@ struct BwdMfmaSlab {
   bf16* GZ;             // [Np, vs]  dloss * G * a'   (token-major; zero for tokens >= N and columns >= V)
   float* dEacc;         // [N, D]
   uint32_t* flags_nv;   // [Np/256, vs/64]  block (256 tokens x 64 vocab) has a significant entry
-  uint32_t* flags_vn;   // [vs/256, Np/64]  block (64 tokens x 256 vocab) has a significant entry;
-                        // starts right after flags_nv (the two are cleared as one array)
+  uint32_t* flags_vn;   // [vs/256, Np/64]  block (64 tokens x 256 vocab) has a significant entry
   int first;            // first slab of the call: dEacc is overwritten instead of added to
   const bf16* Crows;    // row v0 of the classifier as this slab sees it: C + v0 * D, or the slab's
                         // gathered copy when the vocabulary is walked in sorted order
@@ -154,6 +153,12 @@ struct TileListParams {
 };
 hipError_t launch_tile_lists(const TileListParams& p, hipStream_t stream);
 hipError_t launch_bwd_recompute_mfma(const BwdCommon& c, const BwdMfmaSlab& s, hipStream_t stream);
+// Filter flags of the MFMA path: every slab has its own region of `region_words` words
+// ([Np/256, vs/64] then [vs/256, Np/64]); all are cleared once before the first slab and
+// counted once after the last.
+hipError_t launch_zero_flags(uint32_t* flags, int64_t words, hipStream_t stream);
+hipError_t launch_count_flags(const uint32_t* flags, int64_t region_words, int slabs, int n_tiles, int vs, int V,
+                              FilterStats* stats, hipStream_t stream);
 hipError_t launch_bwd_dE_mfma(const BwdCommon& c, const BwdMfmaSlab& s, hipStream_t stream);
 hipError_t launch_bwd_dC_mfma(const BwdCommon& c, const BwdMfmaSlab& s, void* out_dC, hipStream_t stream);
 

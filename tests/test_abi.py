@@ -64,7 +64,8 @@ def test_backward_workspace_is_bounded_by_the_slab_not_the_vocabulary():
     rec = L.cce_workspace_bytes(L.CCE_OP_BACKWARD, N, D, 256000, o)
     rec2 = L.cce_workspace_bytes(L.CCE_OP_BACKWARD, N, D, 1024000, o)
     mn = L.cce_workspace_bytes(L.CCE_OP_BACKWARD_MIN, N, D, 256000, o)
-    assert rec == rec2 and 0 < mn < rec
+    # the only |V|-dependent part is one 4-byte filter flag per 256 x 64 and per 64 x 256 block of logits
+    assert 0 <= rec2 - rec <= N * (1024000 - 256000) // 2048 + 4096 and 0 < mn < rec
     assert rec < N * 256000 * 2 / 5        # far below even a bf16 logit matrix
     assert L.cce_workspace_bytes(99, N, D, 256000, o) == 0
     assert L.cce_workspace_bytes(L.CCE_OP_FORWARD, 0, D, 256000, o) == 0
