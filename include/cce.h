@@ -46,7 +46,8 @@ typedef enum cce_status {
   CCE_OK = 0,
   CCE_EINVAL = -1,       /* null / misaligned pointer, non-positive size, bad softcap or eps */
   CCE_EWORKSPACE = -2,   /* opts->workspace missing or smaller than the minimum */
-  CCE_EUNSUPPORTED = -3, /* unknown dtype or flag */
+  CCE_EUNSUPPORTED = -3, /* unknown dtype or flag, or a size beyond the kernels' 32-bit offsets
+                            (backward on the MFMA path: N * D * 2 bytes must stay below 4 GiB) */
   CCE_EHIP = -4          /* a HIP runtime call failed; see cce_strerror */
 } cce_status;
 

@@ -138,6 +138,8 @@ int check_common(const void* E, const void* C, const int64_t* targets, int64_t N
   if (o->workspace && !aligned(o->workspace, 256)) return CCE_EINVAL;
   if ((o->flags & CCE_SKIP_TILES) && o->block_max) {
     if (!aligned(o->block_max, 256)) return CCE_EINVAL;
+    // the record is addressed with 32-bit element offsets
+    if ((uint64_t)((V + 127) / 128) * (uint64_t)round_up(N, 256) >= ((uint64_t)1 << 31)) return CCE_EUNSUPPORTED;
     if (o->block_max_bytes < block_max_bytes(N, V)) return CCE_EWORKSPACE;
   }
   return CCE_OK;
@@ -397,6 +399,9 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
   float* dEacc = (float*)(ws + plan.off_dEacc);
 
   if (mfma) {
+    // the gradient products address E and a slab of C with 32-bit byte offsets
+    if ((uint64_t)N * (uint64_t)D * 2 >= ((uint64_t)1 << 32) || (uint64_t)vs * (uint64_t)D * 2 >= ((uint64_t)1 << 32))
+      return CCE_EUNSUPPORTED;
     Helpers* h = nullptr;
     st = helpers_for_device(&h);
     if (st != CCE_OK) return st;

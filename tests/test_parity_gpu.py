@@ -293,3 +293,50 @@ def test_plain_entry_points_use_library_workspace(cce):
     assert rel_fro(f64(dE), rdE) <= TOL_GRAD and rel_fro(f64(dC), rdC) <= TOL_GRAD
     total, kept = L.cce_backward_filter_stats()
     assert total > 0
+
+
+def test_calls_on_a_side_stream_and_under_graph_capture(cce):
+    """The entry points take any stream and can be captured into a HIP graph: the helper streams of
+    the backward pass fork from and join back into the capturing stream, nothing is allocated and
+    no memset node is recorded.  Every replay is checked against the eager result."""
+    w = make("gemma2_2b", N=600, D=128, V=7000)
+    E, C, t = to_device(w)
+    dloss = torch.from_numpy(w.mean_dloss()).cuda()
+    o0 = L.make_opts(L.CCE_BF16)
+    ws_f = workspace(L.cce_workspace_bytes(L.CCE_OP_FORWARD, w.N, w.D, w.V, o0))
+    ws_b = workspace(L.cce_workspace_bytes(L.CCE_OP_BACKWARD, w.N, w.D, w.V, o0))
+    loss, lse = torch.empty(w.N, device="cuda"), torch.empty(w.N, device="cuda")
+    dE, dC = torch.empty_like(E), torch.empty_like(C)
+
+    def step(stream):
+        of = L.make_opts(L.CCE_BF16, workspace=ws_f, stream=stream.cuda_stream)
+        ob = L.make_opts(L.CCE_BF16, workspace=ws_b, stream=stream.cuda_stream)
+        L.cce_forward_ex(E, C, t, w.softcap, w.ignore_index, of, out_loss=loss, out_lse=lse)
+        L.cce_backward_ex(E, C, t, lse, dloss, w.softcap, w.ignore_index, ob, out_dE=dE, out_dC=dC)
+
+    def eager():
+        step(torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        return loss.clone(), dE.clone(), dC.clone()
+
+    ref0 = eager()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    step(side)
+    side.synchronize()
+    assert torch.equal(loss, ref0[0]) and torch.equal(dE, ref0[1]) and torch.equal(dC, ref0[2])
+
+    g = torch.cuda.CUDAGraph()
+    cap = torch.cuda.Stream()
+    cap.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(g, stream=cap):
+        step(cap)
+    E_orig = E.clone()
+    for k in range(3):
+        E.copy_(E_orig.roll(k + 1, 0))             # new inputs for every replay
+        ref = eager()
+        loss.zero_(); dE.zero_(); dC.zero_()       # eager work and a synchronisation between replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(loss, ref[0]) and torch.equal(dE, ref[1]) and torch.equal(dC, ref[2]), "replay %d" % k
