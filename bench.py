@@ -7,6 +7,8 @@ whole-job throughput, a roofline object for the forward matmul-LSE kernel (bf16 
 bound) and the fp64 CPU oracle timed on a bounded sample of the same workload.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+  python bench.py --sweep      prints a markdown table over the paper's model shapes (Table A3) and
+                               batch sizes (Fig. A1 / A2) instead of the JSON line
 """
 import argparse
 import json
@@ -50,6 +52,64 @@ def cpu_baseline(w, rows):
             "host_cores_visible": len(os.sched_getaffinity(0))}
 
 
+SWEEP_SHAPES = [  # name, D, |V|, soft-cap   (Table A3 and the memory table A4)
+    ("Gemma-2 2B", 2304, 256000, 30.0), ("Gemma-2 9B", 3584, 256000, 30.0), ("Gemma-2 27B", 4608, 256000, 30.0),
+    ("Mistral NeMo", 5120, 131072, 0.0), ("Phi-3.5 mini", 3072, 32064, 0.0), ("Qwen-2.5 7B", 3584, 152064, 0.0),
+    ("Qwen-2.5 32B", 5120, 152064, 0.0), ("Llama-3 8B", 4096, 128256, 0.0)]
+
+
+def sweep():
+    """Forward / dense backward / filtered backward over model shapes at N = 8192 and over batch sizes."""
+    import torch
+    import paper_2411_09009_amd as L
+    L.load()
+    dev = torch.device("cuda:0")
+
+    def timed(fn, iters):
+        fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(iters):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        return sum(ts) / len(ts)
+
+    def run(name, N, D, V, cap, iters):
+        g = torch.Generator(device=dev)
+        g.manual_seed(0)
+        E = torch.randn(N, D, device=dev, generator=g)
+        E = (E / E.pow(2).mean(1, keepdim=True).sqrt()).to(torch.bfloat16)
+        C = (torch.randn(V, D, device=dev, generator=g) * 0.02).to(torch.bfloat16)
+        t = torch.randint(0, V, (N,), device=dev, generator=g)
+        dl = torch.full((N,), 1.0 / N, device=dev)
+        o = L.make_opts(L.CCE_BF16)
+        ws = torch.empty(L.cce_workspace_bytes(L.CCE_OP_FORWARD, N, D, V, o), dtype=torch.uint8, device=dev)
+        wb = torch.empty(L.cce_workspace_bytes(L.CCE_OP_BACKWARD, N, D, V, o), dtype=torch.uint8, device=dev)
+        loss, lse = torch.empty(N, device=dev), torch.empty(N, device=dev)
+        dE, dC = torch.empty_like(E), torch.empty_like(C)
+        of = L.make_opts(L.CCE_BF16, workspace=ws)
+        res = [timed(lambda: L.cce_forward_ex(E, C, t, cap, -100, of, out_loss=loss, out_lse=lse), iters)]
+        for eps in (0.0, None):
+            ob = L.make_opts(L.CCE_BF16, filter_eps=eps, workspace=wb)
+            res.append(timed(lambda: L.cce_backward_ex(E, C, t, lse, dl, cap, -100, ob, out_dE=dE, out_dC=dC), iters))
+        fl = 2.0 * N * D * V
+        print("| %s | %d | %d | %d | %.2f | %.0f | %.2f | %.0f | %.2f | %.0f | %.0f |"
+              % (name, N, D, V, res[0], fl / res[0] / 1e9, res[1], 3 * fl / res[1] / 1e9, res[2],
+                 N / ((res[0] + res[1]) * 1e-3) / 1e3, wb.numel() / 1e6), flush=True)
+
+    print("| model shape | N | D | V | fwd ms | fwd TFLOP/s | bwd dense ms | bwd dense TFLOP/s | bwd filtered ms "
+          "| fwd+bwd dense k tok/s | bwd workspace MB |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|")
+    for nm, D, V, cap in SWEEP_SHAPES:
+        run(nm, 8192, D, V, cap, 4)
+    for N in (1024, 2048, 4096, 16384, 32768, 65536):
+        run("Gemma-2 2B", N, 2304, 256000, 30.0, 3)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -58,11 +118,15 @@ def main():
     ap.add_argument("--workload", default="gemma2_2b")
     ap.add_argument("--cpu-rows", type=int, default=1536)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (sharding is described in DESIGN.md); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
+    if args.sweep:
+        sweep()
+        return
 
     import torch
     import paper_2411_09009_amd as L
