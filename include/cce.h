@@ -68,6 +68,13 @@ enum {
                                 rows.  The forward pass ignores the flag. */
   CCE_PLAIN_KERNELS = 1u << 3, /* run the plain fp32-FMA kernels instead of the MFMA ones (always used
                                 for CCE_F32 and for shapes the MFMA kernels do not take) */
+  CCE_COMPACT_IGNORED = 1u << 5, /* remove ignored tokens before the work (Appendix B): the kernels run on a
+                                compacted copy of the rows of E whose target is valid, so the cost scales
+                                with the number of valid tokens.  Loss, dE and dC are unchanged (loss and dE
+                                rows of ignored tokens are 0); out_lse of ignored tokens is then unspecified.
+                                Forward and backward are independent in this (either may set it; with
+                                CCE_SKIP_TILES both must agree).  bf16 MFMA path only, ignored otherwise.
+                                Costs one copy of E in the workspace. */
   CCE_SKIP_TILES = 1u << 4    /* forward: also record, in opts->block_max, the largest logit of every token
                                 within each 128-wide vocabulary block; backward (with both CCE_FILTER_* set
                                 and filter_eps > 0): do not even recompute the logit tiles in which that

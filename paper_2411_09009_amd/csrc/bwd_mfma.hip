@@ -31,9 +31,11 @@ namespace {
 __global__ __launch_bounds__(256) void tile_flag_kernel(TileListParams p) {
   const int vt = blockIdx.x, nt = blockIdx.y;
   const int tok = nt * 256 + threadIdx.x;
+  const int n_tokens = p.n_dev ? *p.n_dev : p.N;
   bool sig = false;
-  if (tok < p.N) {
-    const int64_t t = p.targets[tok];
+  if (tok < n_tokens) {
+    const int orig = p.idx ? p.idx[tok] : tok;
+    const int64_t t = p.targets[orig];
     if (t != p.ignore_index && t >= 0 && t < p.V) {
       const int b0 = vt * 2, blocks = (p.V + 127) / 128;
       uint32_t u0 = p.block_max[(int64_t)b0 * p.stride + tok];
@@ -42,7 +44,7 @@ __global__ __launch_bounds__(256) void tile_flag_kernel(TileListParams p) {
         uint32_t u1 = p.block_max[(int64_t)(b0 + 1) * p.stride + tok];
         a = fmaxf(a, __uint_as_float(u1 << 16));
       }
-      sig = (a - p.lse[tok] >= p.log_eps) || (t >= (int64_t)vt * 256 && t < (int64_t)vt * 256 + 256);
+      sig = (a - p.lse[orig] >= p.log_eps) || (t >= (int64_t)vt * 256 && t < (int64_t)vt * 256 + 256);
     }
   }
   const bool any = __syncthreads_or(sig);
@@ -85,11 +87,12 @@ constexpr int kMaxKSteps = 2048;   // longest filtered contraction: 131072 / 64
 // LIST: the workgroup takes an equal share of the slab's work list (tiles the filter cannot
 // skip) instead of a fixed rectangle of tiles.
 template <int MODE, bool LIST>
-__global__ __launch_bounds__(kThreads) void bwd_recompute_mfma_kernel(BwdCommon c, BwdMfmaSlab sl, XcdMap map,
-                                                                      int tiles_per_split) {
+__global__ __launch_bounds__(kThreads) void bwd_recompute_mfma_kernel(BwdCommon c, BwdMfmaSlab sl, SplitPlan plan,
+                                                                      int want_wgs) {
   __shared__ __attribute__((aligned(1024))) char lds[kLdsBytes + 8 * 4096];   // operand ring + store staging
   TileCoords tc;
   tc.init();
+  if (c.n_dev) c.N = *c.n_dev;   // ignored tokens removed: E holds this many tokens
   const int v_tiles = sl.vs / kTileR;
   const int64_t ld_bytes = (int64_t)c.D * 2;
   const int KT = c.D / kTileK;
@@ -105,10 +108,14 @@ __global__ __launch_bounds__(kThreads) void bwd_recompute_mfma_kernel(BwdCommon 
     if (e0 >= e1) return;
     n_tile = (int)(sl.tile_list[e0] >> 16);
   } else {
+    if (c.n_dev) {
+      if (c.N <= 0) return;
+      plan = make_split_plan(c.N, v_tiles, want_wgs, 1 << 30);   // planned again for the tokens present
+    }
     int split;
-    if (!xcd_map_decode(map, blockIdx.x, n_tile, split)) return;
-    t0 = split * tiles_per_split;
-    t1 = min(t0 + tiles_per_split, v_tiles);
+    if (!xcd_map_decode(plan.map, blockIdx.x, n_tile, split)) return;
+    t0 = split * plan.tiles_per_split;
+    t1 = min(t0 + plan.tiles_per_split, v_tiles);
   }
   int n0 = n_tile * kTileC;
 
@@ -124,11 +131,12 @@ __global__ __launch_bounds__(kThreads) void bwd_recompute_mfma_kernel(BwdCommon 
       lam[cb] = 0.f;
       tgt[cb] = -1;
       if (n < c.N) {
-        const int64_t t = c.targets[n];
+        const int o = c.idx ? c.idx[n] : n;
+        const int64_t t = c.targets[o];
         if (t != c.ignore_index && t >= 0 && t < c.V) {
           tgt[cb] = (int)t;
-          lam[cb] = c.dloss[n];
-          lse2[cb] = c.lse[n] * kLog2e;
+          lam[cb] = c.dloss[o];
+          lse2[cb] = c.lse[o] * kLog2e;
         }
       }
     }
@@ -279,10 +287,13 @@ __global__ __launch_bounds__(kThreads) void bwd_product_mfma_kernel(BwdCommon c,
   __shared__ int kcount_s;
   TileCoords tc;
   tc.init();
+  if (c.n_dev) c.N = *c.n_dev;   // ignored tokens removed: E and GZ hold this many tokens
   int tile_r, tile_c;   // a = 256-wide slice of D, b = token tile (dE) or vocabulary tile (dC)
   if (!xcd_map_decode(map, blockIdx.x, tile_r, tile_c)) return;
   const int d0 = tile_r * kTileR, c0 = tile_c * kTileC;
-  const int K = DC ? sl.Np : sl.vs;
+  if (!DC && c0 >= c.N) return;   // a token tile past the tokens present
+  // token tiles past the tokens present were not recomputed: the contraction over tokens stops before them
+  const int K = DC ? (c.N + kTileC - 1) / kTileC * kTileC : sl.vs;
   // P is always K-major: E [N, D] contracted over tokens (dC) or the slab's rows of C [vs, D]
   // contracted over the vocabulary (dE); its tile is columns d0 .. d0 + 255 of every K-row.
   // Q is GZ [Np, vs]: K-major for dC (columns = vocabulary tile), K-contiguous for dE (rows = token tile).
@@ -295,7 +306,7 @@ __global__ __launch_bounds__(kThreads) void bwd_product_mfma_kernel(BwdCommon c,
 
   int kcount = ksteps;
   if (FILTERED) {
-    const uint32_t* flags = (DC ? sl.flags_vn : sl.flags_nv) + (int64_t)tile_c * ksteps;
+    const uint32_t* flags = (DC ? sl.flags_vn : sl.flags_nv) + (int64_t)tile_c * ((DC ? sl.Np : sl.vs) / kTileK);
     if (tc.wave == 0) {
       int count = 0;
       for (int base = 0; base < ksteps; base += 64) {
@@ -397,8 +408,9 @@ __global__ __launch_bounds__(kThreads) void bwd_product_mfma_kernel(BwdCommon c,
 // counts the (256 token x 64 vocabulary) filter blocks of every slab and how many were kept;
 // one workgroup per slab, whose flags start at flags + slab * region_words
 __global__ __launch_bounds__(256) void count_flags_kernel(const uint32_t* flags, int64_t region_words, int n_tiles,
-                                                          int vs, int V, FilterStats* stats) {
+                                                          int vs, int V, FilterStats* stats, const int* n_dev) {
   const int slab = blockIdx.x;
+  if (n_dev) n_tiles = (*n_dev + 255) / 256;   // token tiles actually present
   const int v0 = slab * vs;
   const int vs_this = min(vs, (V - v0 + 255) / 256 * 256);
   const int vsteps = vs_this / 64;
@@ -436,27 +448,23 @@ hipError_t launch_tile_lists(const TileListParams& p, hipStream_t stream) {
 
 hipError_t launch_bwd_recompute_mfma(const BwdCommon& c, const BwdMfmaSlab& s, hipStream_t stream) {
   const int n_tiles = s.Np / kTileC, v_tiles = s.vs / kTileR;
-  int splits = (256 + n_tiles - 1) / n_tiles;
-  if (splits > v_tiles) splits = v_tiles;
-  if (splits < 1) splits = 1;
-  int tps = (v_tiles + splits - 1) / splits;
-  splits = (v_tiles + tps - 1) / tps;
-  const XcdMap map = make_xcd_map(n_tiles, splits);
+  const int want = 256;
+  const SplitPlan plan = make_split_plan(c.N, v_tiles, want, 1 << 30);
   if (s.tile_list) {
     // one share of the work list per CU, at most one per tile
     int groups = 256;
     if (groups > n_tiles * v_tiles) groups = (n_tiles * v_tiles + kXcds - 1) / kXcds * kXcds;
     dim3 grid(groups);
     if (c.softcap > 0.f)
-      hipLaunchKernelGGL((bwd_recompute_mfma_kernel<kCap, true>), grid, dim3(kThreads), 0, stream, c, s, map, tps);
+      hipLaunchKernelGGL((bwd_recompute_mfma_kernel<kCap, true>), grid, dim3(kThreads), 0, stream, c, s, plan, want);
     else
-      hipLaunchKernelGGL((bwd_recompute_mfma_kernel<kNoCap, true>), grid, dim3(kThreads), 0, stream, c, s, map, tps);
+      hipLaunchKernelGGL((bwd_recompute_mfma_kernel<kNoCap, true>), grid, dim3(kThreads), 0, stream, c, s, plan, want);
   } else {
-    dim3 grid(xcd_map_grid(map));
+    dim3 grid(c.n_dev ? split_plan_max_grid(c.N, v_tiles, want, 1 << 30) : xcd_map_grid(plan.map));
     if (c.softcap > 0.f)
-      hipLaunchKernelGGL((bwd_recompute_mfma_kernel<kCap, false>), grid, dim3(kThreads), 0, stream, c, s, map, tps);
+      hipLaunchKernelGGL((bwd_recompute_mfma_kernel<kCap, false>), grid, dim3(kThreads), 0, stream, c, s, plan, want);
     else
-      hipLaunchKernelGGL((bwd_recompute_mfma_kernel<kNoCap, false>), grid, dim3(kThreads), 0, stream, c, s, map, tps);
+      hipLaunchKernelGGL((bwd_recompute_mfma_kernel<kNoCap, false>), grid, dim3(kThreads), 0, stream, c, s, plan, want);
   }
   return hipGetLastError();
 }
@@ -469,8 +477,9 @@ hipError_t launch_zero_flags(uint32_t* flags, int64_t words, hipStream_t stream)
 }
 
 hipError_t launch_count_flags(const uint32_t* flags, int64_t region_words, int slabs, int n_tiles, int vs, int V,
-                              FilterStats* stats, hipStream_t stream) {
-  hipLaunchKernelGGL(count_flags_kernel, dim3(slabs), dim3(256), 0, stream, flags, region_words, n_tiles, vs, V, stats);
+                              FilterStats* stats, const int* n_dev, hipStream_t stream) {
+  hipLaunchKernelGGL(count_flags_kernel, dim3(slabs), dim3(256), 0, stream, flags, region_words, n_tiles, vs, V, stats,
+                     n_dev);
   return hipGetLastError();
 }
 

@@ -128,7 +128,8 @@ int check_common(const void* E, const void* C, const int64_t* targets, int64_t N
                  float softcap, const cce_opts* o) {
   if (!o) return CCE_EINVAL;
   if (o->dtype != CCE_BF16 && o->dtype != CCE_F32) return CCE_EUNSUPPORTED;
-  if (o->flags & ~(uint32_t)(CCE_FILTER_DE | CCE_FILTER_DC | CCE_VOCAB_SORT | CCE_PLAIN_KERNELS | CCE_SKIP_TILES)) return CCE_EUNSUPPORTED;
+  if (o->flags & ~(uint32_t)(CCE_FILTER_DE | CCE_FILTER_DC | CCE_VOCAB_SORT | CCE_PLAIN_KERNELS | CCE_SKIP_TILES |
+                            CCE_COMPACT_IGNORED)) return CCE_EUNSUPPORTED;
   if (!E || !C || !targets) return CCE_EINVAL;
   if (N <= 0 || D <= 0 || V <= 0) return CCE_EINVAL;
   if (N > (int64_t)0x7fff0000 || V > (int64_t)0x7fff0000 || D > (1 << 22)) return CCE_EINVAL;
@@ -148,9 +149,15 @@ int check_common(const void* E, const void* C, const int64_t* targets, int64_t N
 // ------------------------------------------------------------------ forward plan
 struct FwdPlan {
   bool mfma;
-  int splits, tiles_per_split;
+  int splits, tiles_per_split;   // plain path
   int n_tiles, v_tiles;
+  SplitPlan plan;                // MFMA path, for N tokens
+  int want_wgs, round_cap;
+  unsigned grid;
   size_t partial_bytes;
+  // ignored tokens removed (CCE_COMPACT_IGNORED, MFMA path): index list, count, compacted copy of E
+  bool compact;
+  size_t off_idx, off_count, off_Ec;
   size_t total_bytes;
 };
 
@@ -161,17 +168,36 @@ FwdPlan plan_forward(int64_t N, int64_t D, int64_t V, const cce_opts* o) {
   const int cus = cu_count();
   p.n_tiles = (int)((N + tile - 1) / tile);
   p.v_tiles = (int)((V + tile - 1) / tile);
-  // enough vocabulary splits that one "round" of token tiles (at most 32 at a time on the
-  // MFMA path, so that the E tiles in flight stay cache resident) fills every CU
-  int round_tiles = p.mfma ? (p.n_tiles < 32 ? p.n_tiles : 32) : p.n_tiles;
-  int want = p.mfma ? cus : 4 * cus;
-  int splits = (want + round_tiles - 1) / round_tiles;
-  if (splits > p.v_tiles) splits = p.v_tiles;
-  if (splits < 1) splits = 1;
-  p.tiles_per_split = (p.v_tiles + splits - 1) / splits;
-  p.splits = (p.v_tiles + p.tiles_per_split - 1) / p.tiles_per_split;
-  p.partial_bytes = align_up((size_t)p.splits * (size_t)N * sizeof(LsePartial), 256);
+  p.compact = p.mfma && (o->flags & CCE_COMPACT_IGNORED);
+  if (p.mfma) {
+    // enough vocabulary splits that one round of token tiles (at most 32 at a time, so that
+    // the E tiles in flight stay cache resident) fills every CU
+    p.want_wgs = cus;
+    p.round_cap = 32;
+    p.plan = make_split_plan((int)N, p.v_tiles, p.want_wgs, p.round_cap);
+    p.splits = p.plan.splits;
+    p.tiles_per_split = p.plan.tiles_per_split;
+    p.grid = p.compact ? split_plan_max_grid((int)N, p.v_tiles, p.want_wgs, p.round_cap) : xcd_map_grid(p.plan.map);
+  } else {
+    int splits = (4 * cus + p.n_tiles - 1) / p.n_tiles;
+    if (splits > p.v_tiles) splits = p.v_tiles;
+    if (splits < 1) splits = 1;
+    p.tiles_per_split = (p.v_tiles + splits - 1) / splits;
+    p.splits = (p.v_tiles + p.tiles_per_split - 1) / p.tiles_per_split;
+  }
+  size_t rows = (size_t)p.splits * (size_t)N;
+  if (p.compact) {
+    // the device-side plan for fewer tokens uses more splits of fewer rows
+    const size_t most = split_plan_max_partial_rows((int)N, p.v_tiles, p.want_wgs, p.round_cap);
+    if (most > rows) rows = most;
+  }
+  p.partial_bytes = align_up(rows * sizeof(LsePartial), 256);
   p.total_bytes = p.partial_bytes;
+  if (p.compact) {
+    p.off_idx = p.total_bytes;   p.total_bytes += align_up((size_t)N * 4, 256);
+    p.off_count = p.total_bytes; p.total_bytes += 256;
+    p.off_Ec = p.total_bytes;    p.total_bytes += align_up((size_t)round_up(N, 256) * D * 2, 256);
+  }
   return p;
 }
 
@@ -188,10 +214,13 @@ struct BwdPlan {
   size_t sort_temp_bytes;
   // work lists of the recompute kernel (CCE_SKIP_TILES)
   size_t off_tile_flag, off_tile_list, off_tile_count;
+  // ignored tokens removed (CCE_COMPACT_IGNORED)
+  size_t off_idx, off_count, off_Ec;
   size_t total_bytes;
 };
 
-BwdPlan layout_backward(bool mfma, int64_t N, int64_t D, int64_t V, int64_t vs, bool sort, bool lists) {
+BwdPlan layout_backward(bool mfma, int64_t N, int64_t D, int64_t V, int64_t vs, bool sort, bool lists,
+                        bool compact) {
   BwdPlan p{};
   p.mfma = mfma;
   p.vs = vs;
@@ -230,6 +259,11 @@ BwdPlan layout_backward(bool mfma, int64_t N, int64_t D, int64_t V, int64_t vs, 
       p.off_tile_list = off;  off += align_up(slabs * n_tiles * slab_tiles * 4, 256);
       p.off_tile_count = off; off += align_up(slabs * 4, 256);
     }
+    if (compact) {
+      p.off_idx = off;   off += align_up((size_t)N * 4, 256);
+      p.off_count = off; off += 256;
+      p.off_Ec = off;    off += align_up((size_t)p.Np * D * 2, 256);
+    }
   } else {
     p.Np = N;
     p.off_flags[0] = off;
@@ -253,7 +287,7 @@ int64_t recommended_slab(bool mfma, int64_t V) {
 }
 
 // widest slab (multiple of the tile width, at most the recommended one) that fits `bytes`
-int64_t fit_slab(bool mfma, int64_t N, int64_t D, int64_t V, size_t bytes, bool sort, bool lists) {
+int64_t fit_slab(bool mfma, int64_t N, int64_t D, int64_t V, size_t bytes, bool sort, bool lists, bool compact) {
   const int64_t t = slab_tile(mfma);
   int64_t lo = 0, hi = recommended_slab(mfma, V) / t;   // in tiles
   if (mfma) {
@@ -263,7 +297,7 @@ int64_t fit_slab(bool mfma, int64_t N, int64_t D, int64_t V, size_t bytes, bool 
   }
   while (lo < hi) {
     int64_t mid = (lo + hi + 1) / 2;
-    if (layout_backward(mfma, N, D, V, mid * t, sort, lists).total_bytes <= bytes) lo = mid; else hi = mid - 1;
+    if (layout_backward(mfma, N, D, V, mid * t, sort, lists, compact).total_bytes <= bytes) lo = mid; else hi = mid - 1;
   }
   return lo * t;
 }
@@ -300,10 +334,12 @@ size_t cce_workspace_bytes(int op, int64_t N, int64_t D, int64_t V, const cce_op
   const bool mfma = use_mfma(D, opts);
   const bool sort = mfma && (opts->flags & CCE_VOCAB_SORT);
   const bool lists = mfma && !sort && (opts->flags & CCE_SKIP_TILES);
+  const bool compact = mfma && (opts->flags & CCE_COMPACT_IGNORED);
   switch (op) {
     case CCE_OP_FORWARD: return plan_forward(N, D, V, opts).total_bytes;
-    case CCE_OP_BACKWARD: return layout_backward(mfma, N, D, V, recommended_slab(mfma, V), sort, lists).total_bytes;
-    case CCE_OP_BACKWARD_MIN: return layout_backward(mfma, N, D, V, slab_tile(mfma), sort, lists).total_bytes;
+    case CCE_OP_BACKWARD:
+      return layout_backward(mfma, N, D, V, recommended_slab(mfma, V), sort, lists, compact).total_bytes;
+    case CCE_OP_BACKWARD_MIN: return layout_backward(mfma, N, D, V, slab_tile(mfma), sort, lists, compact).total_bytes;
     default: return 0;
   }
 }
@@ -332,17 +368,36 @@ int cce_forward_ex(const void* E, const void* C, const int64_t* targets, int64_t
   if (!opts->workspace || opts->workspace_bytes < plan.total_bytes) return CCE_EWORKSPACE;
   hipStream_t stream = (hipStream_t)opts->stream;
   LsePartial* partial = (LsePartial*)opts->workspace;
+  const int* n_dev = nullptr;
+  const int* idx = nullptr;
+  if (plan.compact) {
+    if ((uint64_t)N * (uint64_t)D * 2 >= ((uint64_t)1 << 32)) return CCE_EUNSUPPORTED;
+    char* ws = (char*)opts->workspace;
+    int* idx_w = (int*)(ws + plan.off_idx);
+    int* count_w = (int*)(ws + plan.off_count);
+    bf16* Ec = (bf16*)(ws + plan.off_Ec);
+    CCE_HIP(launch_compact_tokens(targets, (int)N, (int)V, ignore_index, idx_w, count_w, stream));
+    CCE_HIP(launch_gather_tokens((const bf16*)E, idx_w, count_w, (int)N, (int)D, Ec, stream));
+    // ignored tokens: loss 0 (and lse 0, documented as unspecified)
+    CCE_HIP(launch_fill_f32(out_loss, N, 0.f, stream));
+    CCE_HIP(launch_fill_f32(out_lse, N, 0.f, stream));
+    E = Ec;
+    n_dev = count_w;
+    idx = idx_w;
+  }
 
   if (plan.mfma) {
     FwdMfmaParams p{};
     p.E = (const bf16*)E;
+    p.n_dev = n_dev;
     p.C = (const bf16*)C;
     p.N = (int)N; p.D = (int)D; p.V = (int)V;
     p.softcap = softcap;
     p.partial = partial;
-    p.n_tiles = plan.n_tiles; p.v_tiles = plan.v_tiles;
-    p.splits = plan.splits; p.tiles_per_split = plan.tiles_per_split;
-    p.map = make_xcd_map(plan.n_tiles, plan.splits);
+    p.v_tiles = plan.v_tiles;
+    p.plan = plan.plan;
+    p.want_wgs = plan.want_wgs; p.round_cap = plan.round_cap;
+    p.grid = plan.grid;
     if ((opts->flags & CCE_SKIP_TILES) && opts->block_max) {
       p.block_max = (uint16_t*)opts->block_max;
       p.block_max_stride = (int)round_up(N, 256);
@@ -363,6 +418,8 @@ int cce_forward_ex(const void* E, const void* C, const int64_t* targets, int64_t
   f.softcap = softcap; f.ignore_index = ignore_index;
   f.partial = partial; f.splits = plan.splits;
   f.out_loss = out_loss; f.out_lse = out_lse;
+  f.n_dev = n_dev; f.idx = idx;
+  f.v_tiles = plan.v_tiles; f.want_wgs = plan.want_wgs; f.round_cap = plan.round_cap;
   CCE_HIP(launch_finalize(f, stream));
   return CCE_OK;
 }
@@ -381,9 +438,10 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
   // the workspace is laid out for work lists whenever the flag asks for them (as sized by
   // cce_workspace_bytes); they are used only when nothing but filtered products reads GZ
   const bool lists_layout = mfma && !sort && (opts->flags & CCE_SKIP_TILES);
-  const int64_t vs = fit_slab(mfma, N, D, V, opts->workspace_bytes, sort, lists_layout);
+  const bool compact = mfma && (opts->flags & CCE_COMPACT_IGNORED);
+  const int64_t vs = fit_slab(mfma, N, D, V, opts->workspace_bytes, sort, lists_layout, compact);
   if (vs <= 0) return CCE_EWORKSPACE;
-  const BwdPlan plan = layout_backward(mfma, N, D, V, vs, sort, lists_layout);
+  const BwdPlan plan = layout_backward(mfma, N, D, V, vs, sort, lists_layout, compact);
   hipStream_t stream = (hipStream_t)opts->stream;
   char* ws = (char*)opts->workspace;
 
@@ -413,6 +471,16 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
     if (plan.Np / 64 > kMaxFilteredKSteps) c.filter_dC = 0;
     // helper work may not start before the caller's earlier work on `stream` (which may produce C)
     CCE_HIP(hipEventRecord(h->started, stream));
+    if (compact) {
+      int* idx_w = (int*)(ws + plan.off_idx);
+      int* count_w = (int*)(ws + plan.off_count);
+      bf16* Ec = (bf16*)(ws + plan.off_Ec);
+      CCE_HIP(launch_compact_tokens(targets, (int)N, (int)V, ignore_index, idx_w, count_w, stream));
+      CCE_HIP(launch_gather_tokens((const bf16*)E, idx_w, count_w, (int)N, (int)D, Ec, stream));
+      c.E = Ec;              // the vocabulary sort below keeps using the caller's E (its key is a batch mean)
+      c.n_dev = count_w;
+      c.idx = idx_w;
+    }
     if (sort) {
       VocabSortParams v{};
       v.E = (const bf16*)E; v.C = (const bf16*)C; v.targets = targets;
@@ -440,6 +508,7 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
       t.block_max = (const uint16_t*)opts->block_max;
       t.stride = (int)plan.Np;
       t.targets = targets; t.lse = lse;
+      t.n_dev = c.n_dev; t.idx = c.idx;
       t.N = (int)N; t.V = (int)V; t.ignore_index = ignore_index;
       t.log_eps = logf(c.eps) - 0.02f;   // margin for the fp32 rounding of lse and of the recorded maxima
       t.n_tiles = (int)(plan.Np / 256); t.v_tiles = (int)((V + 255) / 256);
@@ -505,8 +574,8 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
     if (slab >= 2) CCE_HIP(hipStreamWaitEvent(stream, h->dC_done[(int)((slab - 2) % kEventRing)], 0));
     CCE_HIP(hipStreamWaitEvent(stream, h->dE_done[e_last], 0));
     CCE_HIP(launch_count_flags(flags_all, (int64_t)plan.flag_region_words, (int)n_slabs, (int)(plan.Np / 256), (int)vs,
-                               (int)V, c.stats, stream));
-    CCE_HIP(launch_store_dE(dEacc, out_dE, opts->dtype, N * D, stream));
+                               (int)V, c.stats, c.n_dev, stream));
+    CCE_HIP(launch_store_dE(dEacc, out_dE, opts->dtype, N, D, c.idx, c.n_dev, stream));
     return CCE_OK;
   } else {
     BwdPlainSlab s{};
@@ -523,7 +592,7 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
       CCE_HIP(launch_bwd_dE_plain(c, s, stream));
     }
   }
-  CCE_HIP(launch_store_dE(dEacc, out_dE, opts->dtype, N * D, stream));
+  CCE_HIP(launch_store_dE(dEacc, out_dE, opts->dtype, N, D, nullptr, nullptr, stream));
   return CCE_OK;
 }
 

@@ -123,16 +123,20 @@ __global__ __launch_bounds__(kThreads) void fwd_lse_mfma_kernel(FwdMfmaParams p)
 
   // each XCD works on a compact rectangle of (token tile, vocabulary split) pairs, so that
   // its L2 sees every E slice and C slice from several workgroups at about the same time
+  const int n_tokens = p.n_dev ? *p.n_dev : p.N;   // ignored tokens may have been removed from E
+  if (n_tokens <= 0) return;
+  const SplitPlan plan = p.n_dev ? make_split_plan(n_tokens, p.v_tiles, p.want_wgs, p.round_cap) : p.plan;
+  const int partial_stride = p.n_dev ? plan.n_tiles * kTileC : p.N;
   int n_tile, split;
-  if (!xcd_map_decode(p.map, blockIdx.x, n_tile, split)) return;
-  const int vt0 = split * p.tiles_per_split;
-  const int vt1 = min(vt0 + p.tiles_per_split, p.v_tiles);
+  if (!xcd_map_decode(plan.map, blockIdx.x, n_tile, split)) return;
+  const int vt0 = split * plan.tiles_per_split;
+  const int vt1 = min(vt0 + plan.tiles_per_split, p.v_tiles);
   const int n0 = n_tile * kTileC;
   const int64_t ld_bytes = (int64_t)p.D * 2;
   const int KT = p.D / kTileK;
 
   uint32_t offQ[4];
-  dma_offsets(tc, min(kTileC, p.N - n0), ld_bytes, offQ);
+  dma_offsets(tc, min(kTileC, n_tokens - n0), ld_bytes, offQ);
   const char* gQ = (const char*)p.E + (int64_t)n0 * ld_bytes;
 
   // running statistics, base-2 domain: m2 = max(a) * log2(e), s = sum 2^(a*log2e - m2)
@@ -198,12 +202,12 @@ __global__ __launch_bounds__(kThreads) void fwd_lse_mfma_kernel(FwdMfmaParams p)
     float sn = (mn == -INFINITY) ? 0.f
              : a.y * __builtin_amdgcn_exp2f(a.x - mn) + b.y * __builtin_amdgcn_exp2f(b.x - mn);
     int n = n0 + col;
-    if (n < p.N) p.partial[(int64_t)split * p.N + n] = make_float2(mn, sn);
+    if (n < n_tokens) p.partial[(int64_t)split * partial_stride + n] = make_float2(mn, sn);
   }
 }
 
 hipError_t launch_fwd_lse_mfma(const FwdMfmaParams& p, hipStream_t stream) {
-  dim3 grid(xcd_map_grid(p.map)), block(kThreads);
+  dim3 grid(p.grid), block(kThreads);
   const int mode = p.softcap > 40.f ? kCapMax : p.softcap > 0.f ? kCapFixed : kNoCap;
 #define CCE_LAUNCH_FWD(M, R) hipLaunchKernelGGL((fwd_lse_mfma_kernel<M, R>), grid, block, 0, stream, p)
   if (p.block_max) {

@@ -26,7 +26,7 @@ constexpr int kXcds = 8;
 struct XcdMap {
   int dim_a, dim_b, wgs_per_xcd, group_a, group_b;
 };
-inline XcdMap make_xcd_map(int dim_a, int dim_b) {
+__host__ __device__ inline XcdMap make_xcd_map(int dim_a, int dim_b) {
   XcdMap m{dim_a, dim_b, 1, 1, 1};
   const int total = dim_a * dim_b;
   m.wgs_per_xcd = (total + kXcds - 1) / kXcds;
@@ -39,6 +39,7 @@ inline XcdMap make_xcd_map(int dim_a, int dim_b) {
 inline unsigned xcd_map_grid(const XcdMap& m) { return (unsigned)(kXcds * m.wgs_per_xcd); }
 // false: this workgroup is padding (the grid is rounded up to a multiple of 8)
 __device__ inline bool xcd_map_decode(const XcdMap& m, int wg, int& a, int& b) {
+  if (wg / kXcds >= m.wgs_per_xcd) return false;   // the launch may be larger than this map needs
   const int logical = (wg % kXcds) * m.wgs_per_xcd + wg / kXcds;
   if (logical >= m.dim_a * m.dim_b) return false;
   const int per_group = m.group_a * m.group_b;
@@ -49,16 +50,57 @@ __device__ inline bool xcd_map_decode(const XcdMap& m, int wg, int& a, int& b) {
   return a < m.dim_a && b < m.dim_b;
 }
 
+// How the (token tile, vocabulary tile) grid of the forward / recompute kernels is cut into
+// workgroups: every token tile is paired with `splits` contiguous ranges of `tiles_per_split`
+// vocabulary tiles, enough of them that one round of token tiles (at most `round_cap` at a
+// time, so that their E tiles stay cache resident) gives every CU a workgroup.  Computed on
+// the host for N tokens and, when ignored tokens were removed, again on the device for the
+// number actually present (the host launches max_grid workgroups, which covers either).
+struct SplitPlan {
+  int n_tiles, splits, tiles_per_split;
+  XcdMap map;
+};
+__host__ __device__ inline SplitPlan make_split_plan(int n_tokens, int v_tiles, int want_wgs, int round_cap) {
+  SplitPlan p{};
+  p.n_tiles = (n_tokens + 255) / 256;
+  if (p.n_tiles < 1) p.n_tiles = 1;
+  const int round_tiles = p.n_tiles < round_cap ? p.n_tiles : round_cap;
+  int splits = want_wgs / round_tiles;   // rounded down: a round must not exceed the CUs by a few workgroups
+  if (splits > v_tiles) splits = v_tiles;
+  if (splits < 1) splits = 1;
+  p.tiles_per_split = (v_tiles + splits - 1) / splits;
+  p.splits = (v_tiles + p.tiles_per_split - 1) / p.tiles_per_split;
+  p.map = make_xcd_map(p.n_tiles, p.splits);
+  return p;
+}
+// workgroups to launch so that the plan of any token count up to n_tokens fits
+inline unsigned split_plan_max_grid(int n_tokens, int v_tiles, int want_wgs, int round_cap) {
+  const int n_tiles = (n_tokens + 255) / 256;
+  int64_t most = (int64_t)want_wgs + (n_tiles < round_cap ? n_tiles : round_cap);     // up to round_cap token tiles
+  const int64_t big = (int64_t)n_tiles * ((want_wgs + round_cap - 1) / round_cap);     // more than that
+  if (n_tiles > round_cap && big > most) most = big;
+  if (most > (int64_t)n_tiles * v_tiles) most = (int64_t)n_tiles * v_tiles;
+  return (unsigned)((most + kXcds - 1) / kXcds * kXcds + kXcds);
+}
+// rows of the per-split partial buffer that plan can address (stride = tokens rounded up to 256)
+inline size_t split_plan_max_partial_rows(int n_tokens, int v_tiles, int want_wgs, int round_cap) {
+  return (size_t)split_plan_max_grid(n_tokens, v_tiles, want_wgs, round_cap) * 256;
+}
+
 // ---- forward, MFMA path ------------------------------------------------------
 struct FwdMfmaParams {
   const bf16* E;        // [N, D]
   const bf16* C;        // [V, D]
   int N, D, V;
   float softcap;        // 0 = none
-  LsePartial* partial;  // [splits, N]
-  int n_tiles, v_tiles; // ceil(N / 256), ceil(V / 256)
-  int splits, tiles_per_split;
-  XcdMap map;              // a = token tile, b = vocabulary split
+  LsePartial* partial;  // [splits, partial_stride]
+  int v_tiles;          // ceil(V / 256)
+  SplitPlan plan;       // for N tokens (a = token tile, b = vocabulary split)
+  int want_wgs, round_cap;   // the plan's inputs, for the device-side plan
+  unsigned grid;        // workgroups to launch
+  const int* n_dev;        // optional device count of tokens actually present in E (ignored tokens removed):
+                           // the kernel then plans for that many tokens and the partial stride is that
+                           // count rounded up to 256
   uint16_t* block_max;     // optional [ceil(V / 128), block_max_stride] bf16 bits: for every token the largest
                            // (soft-capped) logit within each 128-wide vocabulary block, rounded up; nullptr = off
   int block_max_stride;    // N rounded up to 256
@@ -86,10 +128,15 @@ struct FinalizeParams {
   int N, D, V;
   float softcap;
   int64_t ignore_index;
-  const LsePartial* partial;
+  const LsePartial* partial;   // [splits, N], or as planned on the device when n_dev is set
   int splits;
+  int v_tiles, want_wgs, round_cap;   // MFMA path with n_dev: inputs of the device-side plan
   float* out_loss;
   float* out_lse;
+  // ignored tokens removed: E and partial hold *n_dev tokens, token k being the caller's token idx[k]
+  // (targets and the outputs keep the caller's indexing); nullptr = all N tokens in place
+  const int* n_dev;
+  const int* idx;
 };
 hipError_t launch_finalize(const FinalizeParams& p, hipStream_t stream);
 
@@ -115,6 +162,10 @@ struct BwdCommon {
   float eps;            // 0 = no filtering
   int filter_dE, filter_dC;
   FilterStats* stats;
+  // ignored tokens removed (Appendix B): E holds *n_dev tokens, token k being the caller's token
+  // idx[k]; targets, lse and dloss keep the caller's indexing.  nullptr = all N tokens in place.
+  const int* n_dev;
+  const int* idx;
 };
 
 // MFMA path buffers (bf16).  Np = N rounded up to 256.
@@ -147,6 +198,8 @@ struct TileListParams {
   int n_tiles, v_tiles;        // ceil(N / 256), ceil(V / 256)
   int slab_tiles;              // vocabulary tiles per slab
   int slabs;
+  const int* n_dev;            // ignored tokens removed: see BwdCommon
+  const int* idx;
   uint8_t* tile_flag;          // [n_tiles, v_tiles] scratch
   uint32_t* tile_list;         // [slabs, n_tiles * slab_tiles] out
   uint32_t* tile_count;        // [slabs] out
@@ -158,7 +211,7 @@ hipError_t launch_bwd_recompute_mfma(const BwdCommon& c, const BwdMfmaSlab& s, h
 // counted once after the last.
 hipError_t launch_zero_flags(uint32_t* flags, int64_t words, hipStream_t stream);
 hipError_t launch_count_flags(const uint32_t* flags, int64_t region_words, int slabs, int n_tiles, int vs, int V,
-                              FilterStats* stats, hipStream_t stream);
+                              FilterStats* stats, const int* n_dev, hipStream_t stream);
 hipError_t launch_bwd_dE_mfma(const BwdCommon& c, const BwdMfmaSlab& s, hipStream_t stream);
 hipError_t launch_bwd_dC_mfma(const BwdCommon& c, const BwdMfmaSlab& s, void* out_dC, hipStream_t stream);
 
@@ -198,8 +251,19 @@ hipError_t launch_vocab_sort(const VocabSortParams& p, hipStream_t stream);
 // out[r][:] = C[perm[p0 + r]][:], r < rows (D a multiple of 8)
 hipError_t launch_gather_rows(const bf16* C, const int* perm, int p0, int rows, int D, bf16* out, hipStream_t stream);
 
-// dEacc (fp32 [N, D]) -> out_dE in the storage dtype.
-hipError_t launch_store_dE(const float* dEacc, void* out_dE, int dtype, int64_t count, hipStream_t stream);
+// dEacc (fp32 [N, D]) -> out_dE in the storage dtype.  With idx / n_dev (ignored tokens removed)
+// row k of dEacc goes to row idx[k] of out_dE for k < *n_dev and every other row is zeroed.
+hipError_t launch_store_dE(const float* dEacc, void* out_dE, int dtype, int64_t N, int64_t D, const int* idx,
+                           const int* n_dev, hipStream_t stream);
+
+// ---- removing ignored tokens (Appendix B) ---------------------------------------
+// idx[k] = index of the k-th token whose target is valid (in order), *count = their number
+hipError_t launch_compact_tokens(const int64_t* targets, int N, int V, int64_t ignore_index, int* idx, int* count,
+                                 hipStream_t stream);
+// out[k][:] = E[idx[k]][:] for k < *count (bf16, D a multiple of 8)
+hipError_t launch_gather_tokens(const bf16* E, const int* idx, const int* count, int N, int D, bf16* out,
+                                hipStream_t stream);
+hipError_t launch_fill_f32(float* p, int64_t count, float value, hipStream_t stream);
 hipError_t launch_clear_stats(FilterStats* stats, hipStream_t stream);
 
 }  // namespace cce

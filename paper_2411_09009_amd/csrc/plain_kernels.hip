@@ -107,18 +107,28 @@ __global__ __launch_bounds__(kBlock) void finalize_kernel(FinalizeParams p) {
   const T* C = (const T*)p.C;
   const int lane = threadIdx.x & 63;
   const int n = blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
-  if (n >= p.N) return;
+  int n_tokens = p.N, splits = p.splits, stride = p.N;
+  if (p.n_dev) {
+    // ignored tokens removed: the forward kernel planned its splits for the tokens present
+    n_tokens = *p.n_dev;
+    if (n >= n_tokens) return;
+    const SplitPlan plan = make_split_plan(n_tokens, p.v_tiles, p.want_wgs, p.round_cap);
+    splits = plan.splits;
+    stride = plan.n_tiles * 256;
+  }
+  if (n >= n_tokens) return;
+  const int o = p.idx ? p.idx[n] : n;    // the caller's index of this token
   float m2 = -INFINITY;
-  for (int sp = lane; sp < p.splits; sp += 64) m2 = fmaxf(m2, p.partial[(int64_t)sp * p.N + n].x);
+  for (int sp = lane; sp < splits; sp += 64) m2 = fmaxf(m2, p.partial[(int64_t)sp * stride + n].x);
   for (int o = 32; o > 0; o >>= 1) m2 = fmaxf(m2, __shfl_xor(m2, o));
   float s = 0.f;
-  for (int sp = lane; sp < p.splits; sp += 64) {
-    LsePartial q = p.partial[(int64_t)sp * p.N + n];
+  for (int sp = lane; sp < splits; sp += 64) {
+    LsePartial q = p.partial[(int64_t)sp * stride + n];
     if (q.y > 0.f) s += q.y * exp2f(q.x - m2);
   }
   for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
   const float lse = (m2 + log2f(s)) * kLn2;
-  const int64_t tgt = p.targets[n];
+  const int64_t tgt = p.targets[o];
   const bool valid = tgt != p.ignore_index && tgt >= 0 && tgt < p.V;
   float dot = 0.f;
   if (valid) {
@@ -128,8 +138,8 @@ __global__ __launch_bounds__(kBlock) void finalize_kernel(FinalizeParams p) {
     for (int o = 32; o > 0; o >>= 1) dot += __shfl_xor(dot, o);
   }
   if (lane == 0) {
-    p.out_lse[n] = lse;
-    p.out_loss[n] = valid ? lse - softcap_fn(dot, p.softcap) : 0.f;
+    p.out_lse[o] = lse;
+    p.out_loss[o] = valid ? lse - softcap_fn(dot, p.softcap) : 0.f;
   }
 }
 
@@ -250,6 +260,70 @@ __global__ void store_dE_kernel(const float* __restrict__ acc, T* __restrict__ o
   for (; i < count; i += stride) out[i] = from_f<T>(acc[i]);
 }
 
+// ignored tokens removed: row k of acc belongs to the caller's token idx[k]
+template <typename T>
+__global__ void scatter_dE_kernel(const float* __restrict__ acc, T* __restrict__ out, int64_t D,
+                                  const int* __restrict__ idx, const int* __restrict__ n_dev) {
+  const int64_t count = (int64_t)*n_dev * D;
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < count; i += stride) {
+    const int64_t k = i / D, d = i % D;
+    out[(int64_t)idx[k] * D + d] = from_f<T>(acc[i]);
+  }
+}
+
+template <typename T>
+__global__ void fill_kernel(T* __restrict__ p, int64_t count, T value) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < count; i += stride) p[i] = value;
+}
+
+// Appendix B: the tokens that carry a loss, in order.  One workgroup walks the batch.
+__global__ __launch_bounds__(1024) void compact_tokens_kernel(const int64_t* __restrict__ targets, int N, int V,
+                                                              int64_t ignore_index, int* __restrict__ idx,
+                                                              int* __restrict__ count) {
+  __shared__ int wave_count[16];
+  __shared__ int base_s;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (threadIdx.x == 0) base_s = 0;
+  __syncthreads();
+  for (int i0 = 0; i0 < N; i0 += 1024) {
+    const int i = i0 + threadIdx.x;
+    bool on = false;
+    if (i < N) {
+      const int64_t t = targets[i];
+      on = t != ignore_index && t >= 0 && t < V;
+    }
+    const uint64_t mask = __builtin_amdgcn_ballot_w64(on);
+    if (lane == 0) wave_count[wave] = __builtin_popcountll(mask);
+    __syncthreads();
+    int pos = base_s + __builtin_popcountll(mask & ((1ull << lane) - 1ull));
+    for (int w = 0; w < wave; ++w) pos += wave_count[w];
+    if (on) idx[pos] = i;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      int total = 0;
+      for (int w = 0; w < 16; ++w) total += wave_count[w];
+      base_s += total;
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *count = base_s;
+}
+
+// out[k][:] = E[idx[k]][:] for k < *count, 16 bytes per lane
+__global__ __launch_bounds__(256) void gather_tokens_kernel(const uint4* __restrict__ E, const int* __restrict__ idx,
+                                                            const int* __restrict__ count, int chunks_per_row,
+                                                            uint4* __restrict__ out) {
+  const int64_t total = (int64_t)*count * chunks_per_row;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int k = (int)(i / chunks_per_row), ch = (int)(i % chunks_per_row);
+    out[i] = E[(int64_t)idx[k] * chunks_per_row + ch];
+  }
+}
+
 __global__ void clear_stats_kernel(FilterStats* s) {
   s->blocks_total = 0ull;
   s->blocks_kept = 0ull;
@@ -302,14 +376,49 @@ hipError_t launch_bwd_dC_plain(const BwdCommon& c, const BwdPlainSlab& s, void* 
   return hipGetLastError();
 }
 
-hipError_t launch_store_dE(const float* dEacc, void* out_dE, int dtype, int64_t count, hipStream_t stream) {
+hipError_t launch_store_dE(const float* dEacc, void* out_dE, int dtype, int64_t N, int64_t D, const int* idx,
+                           const int* n_dev, hipStream_t stream) {
+  const int64_t count = N * D;
   int blocks = (int)((count + 1023) / 1024);
   if (blocks > 4096) blocks = 4096;
   if (blocks < 1) blocks = 1;
-  if (dtype == CCE_F32)
+  if (idx) {
+    if (dtype == CCE_F32) {
+      hipLaunchKernelGGL(fill_kernel<float>, dim3(blocks), dim3(256), 0, stream, (float*)out_dE, count, 0.f);
+      hipLaunchKernelGGL(scatter_dE_kernel<float>, dim3(blocks), dim3(256), 0, stream, dEacc, (float*)out_dE, D, idx, n_dev);
+    } else {
+      hipLaunchKernelGGL(fill_kernel<bf16>, dim3(blocks), dim3(256), 0, stream, (bf16*)out_dE, count, (bf16)0.f);
+      hipLaunchKernelGGL(scatter_dE_kernel<bf16>, dim3(blocks), dim3(256), 0, stream, dEacc, (bf16*)out_dE, D, idx, n_dev);
+    }
+  } else if (dtype == CCE_F32) {
     hipLaunchKernelGGL(store_dE_kernel<float>, dim3(blocks), dim3(256), 0, stream, dEacc, (float*)out_dE, count);
-  else
+  } else {
     hipLaunchKernelGGL(store_dE_kernel<bf16>, dim3(blocks), dim3(256), 0, stream, dEacc, (bf16*)out_dE, count);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_compact_tokens(const int64_t* targets, int N, int V, int64_t ignore_index, int* idx, int* count,
+                                 hipStream_t stream) {
+  hipLaunchKernelGGL(compact_tokens_kernel, dim3(1), dim3(1024), 0, stream, targets, N, V, ignore_index, idx, count);
+  return hipGetLastError();
+}
+
+hipError_t launch_gather_tokens(const bf16* E, const int* idx, const int* count, int N, int D, bf16* out,
+                                hipStream_t stream) {
+  const int chunks = D / 8;
+  int64_t blocks = ((int64_t)N * chunks + 255) / 256;
+  if (blocks > 8192) blocks = 8192;
+  hipLaunchKernelGGL(gather_tokens_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, (const uint4*)E, idx, count,
+                     chunks, (uint4*)out);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_f32(float* p, int64_t count, float value, hipStream_t stream) {
+  int blocks = (int)((count + 1023) / 1024);
+  if (blocks > 4096) blocks = 4096;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(fill_kernel<float>, dim3(blocks), dim3(256), 0, stream, p, count, value);
   return hipGetLastError();
 }
 

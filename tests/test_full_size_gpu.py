@@ -107,3 +107,14 @@ def test_full_size_matches_stored_oracle(cce, name):
     assert torch.equal(lse2, lse) and torch.equal(loss2, loss)
     dEk, dCk, stats_k = run_backward(w, E, C, t, lse, dloss, flags=both | L.CCE_SKIP_TILES, block_max=bm)
     assert torch.equal(dEk, dEf) and torch.equal(dCk, dCf) and stats_k == stats_f
+
+    if ign.any():
+        print("ignored tokens removed (Appendix B) %s" % name, flush=True)
+        cf = both | L.CCE_COMPACT_IGNORED
+        loss3, lse3 = run_forward(w, E, C, t, flags=cf)
+        assert torch.equal(loss3, loss)
+        dEc, dCc, _ = run_backward(w, E, C, t, lse, dloss, eps=0.0, flags=cf)
+        assert torch.equal(dEc, dE)
+        cC = rel_fro(rows_of(dCc, vr), ref_dC)
+        print("  compacted: dC rows err %.2e" % cC, flush=True)
+        assert cC <= TOL_GRAD

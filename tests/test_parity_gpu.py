@@ -180,6 +180,50 @@ def test_skipping_tiles_the_filter_drops_changes_nothing(cce, name, N, D, V, kw)
     assert ei.value.status == -2
 
 
+@pytest.mark.parametrize("frac", [0.0, 0.02, 0.6, 1.0])
+def test_removing_ignored_tokens_changes_nothing_but_the_cost(cce, frac):
+    """CCE_COMPACT_IGNORED (Appendix B): the kernels run on the valid tokens only."""
+    w = make("gemma2_2b", N=1100, D=128, V=3000, ignore_frac=frac)
+    E, C, t = to_device(w)
+    both = L.CCE_FILTER_DE | L.CCE_FILTER_DC
+    cmp_ = L.CCE_COMPACT_IGNORED
+    valid = torch.from_numpy(w.targets != w.ignore_index).cuda()
+    loss0, lse0 = run_forward(w, E, C, t)
+    loss1, lse1 = run_forward(w, E, C, t, flags=both | cmp_)
+    assert torch.equal(loss0, loss1)                                  # a token's LSE does not depend on its neighbours
+    assert torch.equal(lse0[valid], lse1[valid])
+    ref_loss, ref_lse, rdE, rdC = oracle_all(w)
+    assert max_rel(f64(loss1), ref_loss) <= TOL_LOSS
+    rng = np.random.default_rng(3)
+    lam = (rng.standard_normal(w.N) * 0.01 + 1.0 / w.N).astype(np.float32)
+    rdE, rdC = O.backward(w.E64(), w.C64(), w.targets, ref_lse, lam.astype(np.float64), w.softcap, w.ignore_index)
+    lam[w.targets == w.ignore_index] = np.nan                          # must not be read
+    dloss = torch.from_numpy(lam).cuda()
+    for eps in (0.0, None):
+        dE0, dC0, st0 = run_backward(w, E, C, t, lse0, dloss, eps=eps)
+        dE1, dC1, st1 = run_backward(w, E, C, t, lse1, dloss, eps=eps, flags=both | cmp_)
+        assert torch.equal(dE0, dE1)                                  # rows of dE are per token
+        assert torch.all(dE1[~valid] == 0)
+        if frac < 1.0:
+            assert rel_fro(f64(dC1), f64(dC0)) <= 2e-3                # other token order in the sums over tokens
+            if eps == 0.0:
+                assert rel_fro(f64(dE1), rdE) <= TOL_GRAD and rel_fro(f64(dC1), rdC) <= TOL_GRAD
+        else:
+            assert torch.all(dC1 == 0) and torch.all(dE1 == 0)
+    # together with tile skipping, vocabulary sorting and narrow slabs
+    bm = torch.empty(L.cce_block_max_bytes(w.N, w.V), dtype=torch.uint8, device="cuda")
+    fl = both | cmp_ | L.CCE_SKIP_TILES
+    loss2, lse2 = run_forward(w, E, C, t, flags=fl, block_max=bm)
+    assert torch.equal(loss2, loss1)
+    dE2, dC2, _ = run_backward(w, E, C, t, lse2, dloss, flags=fl, block_max=bm)
+    dE3, dC3, _ = run_backward(w, E, C, t, lse1, dloss, flags=both | cmp_)
+    assert torch.equal(dE2, dE3) and torch.equal(dC2, dC3)
+    dE4, dC4, _ = run_backward(w, E, C, t, lse1, dloss, eps=0.0, flags=both | cmp_ | L.CCE_VOCAB_SORT,
+                               op=L.CCE_OP_BACKWARD_MIN)
+    dE5, dC5, _ = run_backward(w, E, C, t, lse1, dloss, eps=0.0, flags=both | cmp_)
+    assert torch.equal(dC4, dC5) and rel_fro(f64(dE4), f64(dE5)) <= 2e-3
+
+
 def test_tiny_config_fp32_full_parity(cce):
     """Config 1 (N=256, D=64, V=1024, fp32, 5% ignored): the oracle covers every output."""
     w = make("tiny")
