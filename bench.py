@@ -121,7 +121,7 @@ def main():
     ap.add_argument("--sweep", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (sharding is described in DESIGN.md); "
+        print("bench.py: this build runs on one GPU only (how the path would shard is a design note, not code); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
     if args.sweep:
