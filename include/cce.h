@@ -75,6 +75,10 @@ enum {
                                 Forward and backward are independent in this (either may set it; with
                                 CCE_SKIP_TILES both must agree).  bf16 MFMA path only, ignored otherwise.
                                 Costs one copy of E in the workspace. */
+  CCE_SINGLE_STREAM = 1u << 6, /* backward: enqueue every kernel on the caller's stream.  By default the MFMA
+                                backward spreads a slab's recompute and its two gradient products over
+                                helper streams (joined back before the call returns); this flag gives the
+                                plain sequence, slower, e.g. for per-kernel profiling. */
   CCE_SKIP_TILES = 1u << 4    /* forward: also record, in opts->block_max, the largest logit of every token
                                 within each 128-wide vocabulary block; backward (with both CCE_FILTER_* set
                                 and filter_eps > 0): do not even recompute the logit tiles in which that

@@ -10,7 +10,7 @@ import torch
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libcce.so")
 
 CCE_BF16, CCE_F32 = 0, 1
-CCE_FILTER_DE, CCE_FILTER_DC, CCE_VOCAB_SORT, CCE_PLAIN_KERNELS, CCE_SKIP_TILES, CCE_COMPACT_IGNORED = 1, 2, 4, 8, 16, 32
+CCE_FILTER_DE, CCE_FILTER_DC, CCE_VOCAB_SORT, CCE_PLAIN_KERNELS, CCE_SKIP_TILES, CCE_COMPACT_IGNORED, CCE_SINGLE_STREAM = 1, 2, 4, 8, 16, 32, 64
 CCE_OP_FORWARD, CCE_OP_BACKWARD, CCE_OP_BACKWARD_MIN = 0, 1, 2
 
 

@@ -288,8 +288,12 @@ __global__ __launch_bounds__(kThreads) void bwd_product_mfma_kernel(BwdCommon c,
   TileCoords tc;
   tc.init();
   if (c.n_dev) c.N = *c.n_dev;   // ignored tokens removed: E and GZ hold this many tokens
-  int tile_r, tile_c;   // a = 256-wide slice of D, b = token tile (dE) or vocabulary tile (dC)
+  int tile_r, tile_c;   // a = 256-wide slice of D, b = token tile x part of the slab (dE) or vocabulary tile (dC)
   if (!xcd_map_decode(map, blockIdx.x, tile_r, tile_c)) return;
+  // dE of a small batch has fewer tiles than CUs: the slab's K steps are then cut into ksplit
+  // parts, each with its own fp32 accumulator (summed when dE is stored)
+  const int part = DC ? 0 : tile_c % sl.ksplit;
+  if (!DC) tile_c /= sl.ksplit;
   const int d0 = tile_r * kTileR, c0 = tile_c * kTileC;
   if (!DC && c0 >= c.N) return;   // a token tile past the tokens present
   // token tiles past the tokens present were not recomputed: the contraction over tokens stops before them
@@ -303,15 +307,17 @@ __global__ __launch_bounds__(kThreads) void bwd_product_mfma_kernel(BwdCommon c,
                                                                      // (the matching GZ entries are zero)
   const char* Q = (const char*)sl.GZ + (DC ? (int64_t)c0 * 2 : (int64_t)c0 * ldQ);
   const int ksteps = K / kTileK;
+  const int steps_per_part = DC ? ksteps : (ksteps + sl.ksplit - 1) / sl.ksplit;
+  const int k_lo = min(ksteps, part * steps_per_part), k_hi = min(ksteps, k_lo + steps_per_part);
 
-  int kcount = ksteps;
+  int kcount = k_hi - k_lo;
   if (FILTERED) {
     const uint32_t* flags = (DC ? sl.flags_vn : sl.flags_nv) + (int64_t)tile_c * ((DC ? sl.Np : sl.vs) / kTileK);
     if (tc.wave == 0) {
       int count = 0;
-      for (int base = 0; base < ksteps; base += 64) {
+      for (int base = k_lo; base < k_hi; base += 64) {
         int idx = base + tc.lane;
-        bool on = idx < ksteps && flags[idx] != 0;
+        bool on = idx < k_hi && flags[idx] != 0;
         uint64_t mask = __builtin_amdgcn_ballot_w64(on);
         int pos = count + __builtin_popcountll(mask & ((1ull << tc.lane) - 1ull));
         if (on) klist[pos] = (uint16_t)idx;
@@ -342,7 +348,7 @@ __global__ __launch_bounds__(kThreads) void bwd_product_mfma_kernel(BwdCommon c,
     mma_pipeline<true, DC>(
         tc, lds, kcount, acc,
         [&](StageSrc& src) {
-          int kstep = cursor;
+          int kstep = k_lo + cursor;
           if (FILTERED) {
             // the list lives in LDS; read it past the compiler (it would otherwise wait for
             // every direct load in flight before any LDS access it can see)
@@ -394,7 +400,7 @@ __global__ __launch_bounds__(kThreads) void bwd_product_mfma_kernel(BwdCommon c,
             *(uint2*)(out_dC + (int64_t)out_row[cb] * c.D + d) = packed;
           }
         } else if (col < c.N) {
-          float4* dst = (float4*)(sl.dEacc + (int64_t)col * c.D + d);
+          float4* dst = (float4*)(sl.dEacc + (int64_t)part * sl.dE_part_stride + (int64_t)col * c.D + d);
           if (!sl.first) {
             float4 old = *dst;
             v.x += old.x; v.y += old.y; v.z += old.z; v.w += old.w;
@@ -485,7 +491,7 @@ hipError_t launch_count_flags(const uint32_t* flags, int64_t region_words, int s
 
 hipError_t launch_bwd_dE_mfma(const BwdCommon& c, const BwdMfmaSlab& s, hipStream_t stream) {
   const int tiles_r = (c.D + kTileR - 1) / kTileR;
-  const XcdMap map = make_xcd_map(tiles_r, s.Np / kTileC);
+  const XcdMap map = make_xcd_map(tiles_r, (s.Np / kTileC) * s.ksplit);
   dim3 grid(xcd_map_grid(map));
   if (c.filter_dE && c.eps > 0.f)
     hipLaunchKernelGGL((bwd_product_mfma_kernel<false, true>), grid, dim3(kThreads), 0, stream, c, s, (bf16*)nullptr, map);

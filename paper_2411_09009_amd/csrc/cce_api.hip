@@ -8,7 +8,6 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
-#include <cstdlib>
 #include <mutex>
 
 namespace {
@@ -129,7 +128,7 @@ int check_common(const void* E, const void* C, const int64_t* targets, int64_t N
   if (!o) return CCE_EINVAL;
   if (o->dtype != CCE_BF16 && o->dtype != CCE_F32) return CCE_EUNSUPPORTED;
   if (o->flags & ~(uint32_t)(CCE_FILTER_DE | CCE_FILTER_DC | CCE_VOCAB_SORT | CCE_PLAIN_KERNELS | CCE_SKIP_TILES |
-                            CCE_COMPACT_IGNORED)) return CCE_EUNSUPPORTED;
+                            CCE_COMPACT_IGNORED | CCE_SINGLE_STREAM)) return CCE_EUNSUPPORTED;
   if (!E || !C || !targets) return CCE_EINVAL;
   if (N <= 0 || D <= 0 || V <= 0) return CCE_EINVAL;
   if (N > (int64_t)0x7fff0000 || V > (int64_t)0x7fff0000 || D > (1 << 22)) return CCE_EINVAL;
@@ -202,6 +201,17 @@ FwdPlan plan_forward(int64_t N, int64_t D, int64_t V, const cce_opts* o) {
 }
 
 // ------------------------------------------------------------------ backward plan
+// Small batches: the dE product then has fewer (token tile, D tile) pairs than CUs, and cuts each
+// slab's contraction into this many parts with an accumulator each.
+int dE_ksplit(int64_t N, int64_t D) {
+  const int64_t tiles = (round_up(N, 256) / 256) * (round_up(D, 256) / 256);
+  int64_t k = (256 + tiles / 2) / tiles;
+  if (k < 1) k = 1;
+  if (k > 8) k = 8;
+  return (int)k;
+}
+
+
 struct BwdPlan {
   bool mfma;
   int64_t Np, vs;          // padded token count, slab width
@@ -228,7 +238,7 @@ BwdPlan layout_backward(bool mfma, int64_t N, int64_t D, int64_t V, int64_t vs, 
   if (mfma) {
     p.Np = round_up(N, 256);
     p.off_dEacc = off;
-    off += align_up((size_t)N * D * 4, 256);
+    off += align_up((size_t)dE_ksplit(N, D) * (size_t)N * D * 4, 256);
     {
       const size_t slabs = (size_t)((round_up(V, 256) + vs - 1) / vs);
       p.flag_region_words = (size_t)(p.Np / 256) * (vs / 64) + (size_t)(vs / 256) * (p.Np / 64);
@@ -279,17 +289,23 @@ BwdPlan layout_backward(bool mfma, int64_t N, int64_t D, int64_t V, int64_t vs, 
 
 int64_t slab_tile(bool mfma) { return mfma ? 256 : 64; }
 
-int64_t recommended_slab(bool mfma, int64_t V) {
+// Small batches: the slab widens as the batch shrinks (the GZ slab keeps its size) so that the
+// recompute still has a tile for every CU.
+int64_t recommended_slab(bool mfma, int64_t N, int64_t V) {
   int64_t full = round_up(V, slab_tile(mfma));
   int64_t rec = mfma ? kMfmaSlabCols : kPlainSlabCols;
-  if (const char* e = getenv("CCE_DEBUG_SLAB")) if (mfma) rec = atoll(e);
+  if (mfma) {
+    int64_t widen = 8192 / round_up(N, 256);
+    if (widen > 8) widen = 8;
+    if (widen > 1) rec *= widen;
+  }
   return full < rec ? full : rec;
 }
 
 // widest slab (multiple of the tile width, at most the recommended one) that fits `bytes`
 int64_t fit_slab(bool mfma, int64_t N, int64_t D, int64_t V, size_t bytes, bool sort, bool lists, bool compact) {
   const int64_t t = slab_tile(mfma);
-  int64_t lo = 0, hi = recommended_slab(mfma, V) / t;   // in tiles
+  int64_t lo = 0, hi = recommended_slab(mfma, N, V) / t;   // in tiles
   if (mfma) {
     // the recompute kernel addresses the slab with 32-bit element offsets
     const int64_t cap = (((int64_t)1 << 30) / round_up(N, 256)) / t;
@@ -338,7 +354,7 @@ size_t cce_workspace_bytes(int op, int64_t N, int64_t D, int64_t V, const cce_op
   switch (op) {
     case CCE_OP_FORWARD: return plan_forward(N, D, V, opts).total_bytes;
     case CCE_OP_BACKWARD:
-      return layout_backward(mfma, N, D, V, recommended_slab(mfma, V), sort, lists, compact).total_bytes;
+      return layout_backward(mfma, N, D, V, recommended_slab(mfma, N, V), sort, lists, compact).total_bytes;
     case CCE_OP_BACKWARD_MIN: return layout_backward(mfma, N, D, V, slab_tile(mfma), sort, lists, compact).total_bytes;
     default: return 0;
   }
@@ -467,6 +483,8 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
     BwdMfmaSlab s{};
     s.Np = (int)plan.Np;
     s.dEacc = dEacc;
+    s.ksplit = dE_ksplit(N, D);
+    s.dE_part_stride = N * D;
     // a filtered contraction keeps its list of 64-wide steps in LDS; longer ones run unfiltered
     if (plan.Np / 64 > kMaxFilteredKSteps) c.filter_dC = 0;
     // helper work may not start before the caller's earlier work on `stream` (which may produce C)
@@ -556,7 +574,7 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
       // dC products of consecutive slabs write disjoint rows: they alternate between two
       // streams so that the last, partly filled round of one overlaps the next one's start
       hipStream_t dC_stream = h->product[(slab & 1) ? 2 : 0];
-      static const bool serial = getenv("CCE_DEBUG_SERIAL") != nullptr;
+      const bool serial = (opts->flags & CCE_SINGLE_STREAM) != 0;
       if (serial) { dC_stream = stream; }
       hipStream_t dE_stream = serial ? stream : h->product[1];
       CCE_HIP(hipStreamWaitEvent(dC_stream, h->recomputed[e], 0));
@@ -575,7 +593,7 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
     CCE_HIP(hipStreamWaitEvent(stream, h->dE_done[e_last], 0));
     CCE_HIP(launch_count_flags(flags_all, (int64_t)plan.flag_region_words, (int)n_slabs, (int)(plan.Np / 256), (int)vs,
                                (int)V, c.stats, c.n_dev, stream));
-    CCE_HIP(launch_store_dE(dEacc, out_dE, opts->dtype, N, D, c.idx, c.n_dev, stream));
+    CCE_HIP(launch_store_dE(dEacc, s.ksplit, out_dE, opts->dtype, N, D, c.idx, c.n_dev, stream));
     return CCE_OK;
   } else {
     BwdPlainSlab s{};
@@ -592,7 +610,7 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
       CCE_HIP(launch_bwd_dE_plain(c, s, stream));
     }
   }
-  CCE_HIP(launch_store_dE(dEacc, out_dE, opts->dtype, N, D, nullptr, nullptr, stream));
+  CCE_HIP(launch_store_dE(dEacc, 1, out_dE, opts->dtype, N, D, nullptr, nullptr, stream));
   return CCE_OK;
 }
 

@@ -172,7 +172,9 @@ struct BwdCommon {
 struct BwdMfmaSlab {
   int v0, vs, Np;
   bf16* GZ;             // [Np, vs]  dloss * G * a'   (token-major; zero for tokens >= N and columns >= V)
-  float* dEacc;         // [N, D]
+  float* dEacc;         // [ksplit, N, D]
+  int ksplit;           // parts the dE product cuts a slab's K steps into (>= 1), one accumulator each
+  int64_t dE_part_stride;   // N * D
   uint32_t* flags_nv;   // [Np/256, vs/64]  block (256 tokens x 64 vocab) has a significant entry
   uint32_t* flags_vn;   // [vs/256, Np/64]  block (64 tokens x 256 vocab) has a significant entry
   int first;            // first slab of the call: dEacc is overwritten instead of added to
@@ -251,10 +253,10 @@ hipError_t launch_vocab_sort(const VocabSortParams& p, hipStream_t stream);
 // out[r][:] = C[perm[p0 + r]][:], r < rows (D a multiple of 8)
 hipError_t launch_gather_rows(const bf16* C, const int* perm, int p0, int rows, int D, bf16* out, hipStream_t stream);
 
-// dEacc (fp32 [N, D]) -> out_dE in the storage dtype.  With idx / n_dev (ignored tokens removed)
-// row k of dEacc goes to row idx[k] of out_dE for k < *n_dev and every other row is zeroed.
-hipError_t launch_store_dE(const float* dEacc, void* out_dE, int dtype, int64_t N, int64_t D, const int* idx,
-                           const int* n_dev, hipStream_t stream);
+// Sum of the `parts` accumulators dEacc (fp32 [parts, N, D]) -> out_dE in the storage dtype.  With idx /
+// n_dev (ignored tokens removed) row k goes to row idx[k] of out_dE for k < *n_dev and every other row is zeroed.
+hipError_t launch_store_dE(const float* dEacc, int parts, void* out_dE, int dtype, int64_t N, int64_t D,
+                           const int* idx, const int* n_dev, hipStream_t stream);
 
 // ---- removing ignored tokens (Appendix B) ---------------------------------------
 // idx[k] = index of the k-th token whose target is valid (in order), *count = their number

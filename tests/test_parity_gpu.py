@@ -265,6 +265,10 @@ def test_narrow_slabs_and_small_workspace(cce):
     _, _, rdE, rdC = oracle_all(w)
     assert rel_fro(f64(dE2), rdE) <= TOL_GRAD and rel_fro(f64(dC2), rdC) <= TOL_GRAD
     assert torch.equal(dC, dC2)       # dC rows are final within their slab: identical whatever the slab width
+    # the same kernels in plain sequence on the caller's stream give the same bits
+    dE3, dC3, _ = run_backward(w, E, C, t, lse, dloss, eps=0.0,
+                               flags=L.CCE_FILTER_DE | L.CCE_FILTER_DC | L.CCE_SINGLE_STREAM)
+    assert torch.equal(dE, dE3) and torch.equal(dC, dC3)
     o = L.make_opts(L.CCE_BF16, workspace=workspace(4096))
     with pytest.raises(L.CceError) as ei:
         L.cce_backward_ex(E, C, t, lse, dloss, 0.0, w.ignore_index, o)
