@@ -83,6 +83,8 @@ enum {
                                 within each 128-wide vocabulary block; backward (with both CCE_FILTER_* set
                                 and filter_eps > 0): do not even recompute the logit tiles in which that
                                 record shows no softmax entry can reach filter_eps and which hold no target.
+                                With CCE_COMPACT_IGNORED the record is indexed by compacted token, so
+                                forward and backward must then both set (or both clear) that flag.
                                 The gradients are bit-identical to the filtered backward without the flag
                                 (only tiles whose blocks the filter drops anyway are left out); Alg. 3 / 4
                                 recompute every tile first and test afterwards.  bf16 MFMA path only; ignored
@@ -99,7 +101,7 @@ enum {
 
 typedef struct cce_opts {
   int dtype;              /* CCE_BF16 or CCE_F32 */
-  uint32_t flags;         /* CCE_FILTER_* | CCE_VOCAB_SORT | CCE_PLAIN_KERNELS */
+  uint32_t flags;         /* any of the CCE_* flag bits above */
   float filter_eps;       /* gradient-filter threshold on |softmax - onehot|; 0 disables filtering.
                              The paper's value for bf16 is 2^-12 (Section 4.3). */
   void* workspace;        /* device scratch, 256-byte aligned, owned by the caller */
@@ -120,8 +122,9 @@ void cce_default_opts(int dtype, cce_opts* opts);
  * Forward (Alg. 1 indexed matmul + Alg. 2 linear-log-sum-exp, Eq. 4).
  *   out_lse [N] float:  log sum_j exp(a_ij) for EVERY row, ignored or not.
  *   out_loss[N] float:  out_lse_i - a_{i,x_i} for valid tokens, 0 for ignored ones.
- * Extra device memory: the workspace only, O(N) floats (plus O(V) with
- * CCE_VOCAB_SORT); the logits live in registers / LDS.
+ * Extra device memory: the workspace only, O(N) floats; the logits live in
+ * registers / LDS.  (CCE_COMPACT_IGNORED adds a copy of E, CCE_SKIP_TILES the
+ * caller's block_max record.)
  *
  * cce_forward: bf16 inputs, null stream, library-owned workspace (allocated
  * with hipMalloc on first use per device, grown when a larger problem arrives,
@@ -150,8 +153,11 @@ int cce_forward_ex(const void* E, const void* C, const int64_t* targets,
  * filter_eps in magnitude is left out of the products that have their
  * CCE_FILTER_* bit set.  Block shape is an implementation choice
  * (cce_filter_block reports it).
- * Extra device memory: the workspace, independent of |V|: a slab of the
- * gradient-of-logits matrix plus an fp32 [N, D] accumulator.
+ * Extra device memory: the workspace: two slabs of the gradient-of-logits matrix
+ * (bf16, N x slab width), fp32 [N, D] accumulator(s) and 4 bytes of filter flag per
+ * 256 x 64 and 64 x 256 block of logits - the only part that grows with |V|.
+ * Work that the call spreads over the library's helper streams is joined back into
+ * opts->stream before it returns; the whole call can be captured into a HIP graph.
  *
  * cce_backward: bf16, null stream, filtering on at 2^-12, library-owned workspace.
  */
