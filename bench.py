@@ -277,6 +277,11 @@ def main():
                      "traffic": MEASURED_FWD_TRAFFIC_BYTES.get(w.spec.name),
                      "algorithmic_flop_per_launch": fwd_flop,
                      "mfma_only_loop_tflops_this_box": probe_tflops},
+        "roofline_backward_dense": {"kernel": "bwd_recompute_mfma_kernel + bwd_product_mfma_kernel x2 per slab "
+                                              "(timed as cce_backward_ex, overlapped on three streams)",
+                                    "bound": "mfma", "achieved": bwd_tflops, "peak": MFMA_BF16_PEAK_TFLOPS,
+                                    "unit": "TFLOP/s", "frac": bwd_tflops / MFMA_BF16_PEAK_TFLOPS,
+                                    "algorithmic_flop_per_call": 3.0 * fwd_flop},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, min(args.cpu_rows, N))
