@@ -316,11 +316,106 @@ __device__ inline void mma_pipeline(const TileCoords& tc, char* lds, int nsteps,
   wait_dma();   // the surplus loads must have landed before the LDS is reused or released
 }
 
+// Variant with three P buffers and two Q buffers (all 160 KB of the LDS), for kernels that need
+// no other LDS while the pipeline runs and whose operands are both K-contiguous.  The P loads
+// of stage i+3 and the Q loads of stage i+2 are issued together (Q first) in the last quarter
+// of stage i: P gets two stages to land, only the Q half of a stage is waited for one stage
+// after its issue, and the four newest P loads stay in flight across the barrier, so the
+// memory system is never drained.  Same contract as mma_pipeline.
+constexpr int kLdsBytes3 = 5 * kSliceBytes;
+template <int KSTORE = 0, class Next, class StepDone>
+__device__ inline void mma_pipeline3(const TileCoords& tc, char* lds, int nsteps, f32x16 (&acc)[kRB][kCB], Next next,
+                                     StepDone step_done) {
+  if (nsteps <= 0) return;
+  const uint32_t lds_base = lds_addr(lds);
+  constexpr uint32_t q_area = 3u * kSliceBytes;      // the Q buffers follow the three P buffers
+  bf16x8 p[2][kRB], q[2][kCB];
+  auto issue_p = [&](const StageSrc& s, int buf) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) dma_one(tc, s.gP, s.offP[j], lds + buf * kSliceBytes, j);
+  };
+  auto issue_q = [&](const StageSrc& s, int buf) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) dma_one(tc, s.gQ, s.offQ[j], lds + q_area + buf * kSliceBytes, j);
+  };
+#define CCE_READ_FRAGS3(buf, pbi, qbi, ks)                                                       \
+  {                                                                                              \
+    const uint32_t pa = lds_base + (pbi) * kSliceBytes + tc.p_off[ks];                           \
+    const uint32_t qa = lds_base + q_area + (qbi) * kSliceBytes + (tc.q_off[ks] - kSliceBytes);  \
+    p[buf][0] = lds_read_b128<0>(pa);                                                            \
+    p[buf][1] = lds_read_b128<4096>(pa);                                                         \
+    p[buf][2] = lds_read_b128<8192>(pa);                                                         \
+    p[buf][3] = lds_read_b128<12288>(pa);                                                        \
+    q[buf][0] = lds_read_b128<0>(qa);                                                            \
+    q[buf][1] = lds_read_b128<4096>(qa);                                                         \
+  }
+  // prologue: stage 0 complete, then P1, Q1, P2 in flight; Q2 follows in iteration 0
+  StageSrc sq;
+  next(sq);
+  issue_p(sq, 0);
+  issue_q(sq, 0);
+  wait_dma();
+  __builtin_amdgcn_s_barrier();
+  next(sq);
+  issue_p(sq, 1);
+  issue_q(sq, 1);
+  next(sq);            // stage 2: its Q half is still to be issued
+  issue_p(sq, 2);
+  CCE_READ_FRAGS3(0, 0u, 0u, 0)
+  lds_wait(p[0], q[0]);
+  uint32_t pb = 0, qb = 0;     // buffers of the current stage
+  bool stores_pending = false;
+  for (int i = 0; i < nsteps; ++i) {
+    const uint32_t pn = pb == 2 ? 0 : pb + 1, qn = qb ^ 1;
+    CCE_READ_FRAGS3(1, pb, qb, 1)
+    CCE_MMA8(0)
+    __builtin_amdgcn_sched_barrier(0);
+    lds_wait(p[1], q[1]);
+    CCE_READ_FRAGS3(0, pb, qb, 2)
+    CCE_MMA8(1)
+    __builtin_amdgcn_sched_barrier(0);
+    lds_wait(p[0], q[0]);
+    CCE_READ_FRAGS3(1, pb, qb, 3)
+    CCE_MMA8(0)
+    __builtin_amdgcn_sched_barrier(0);
+    lds_wait(p[1], q[1]);
+    // stage i+1 must have landed: its P (issued two stages ago) and its Q (one stage ago); the
+    // four P loads issued after that Q, and an epilogue's stores after those, may stay in flight
+    if (KSTORE > 0 && stores_pending) wait_dma_except<4 + KSTORE>();
+    else wait_dma_except<4>();
+    __builtin_amdgcn_s_barrier();
+    CCE_READ_FRAGS3(0, pn, qn, 0)
+    StageSrc sp;
+    next(sp);            // stage i + 3
+    char* dstQ = lds + q_area + qb * kSliceBytes;   // the buffers stage i has just left
+    char* dstP = lds + pb * kSliceBytes;
+    pin_acc(acc);
+#pragma unroll
+    for (int rb = 0; rb < kRB; ++rb)
+#pragma unroll
+      for (int cb = 0; cb < kCB; ++cb) {
+        acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p[1][rb], q[1][cb], acc[rb][cb], 0, 0, 0);
+        const int m = rb * kCB + cb;
+        if (m < 4) dma_one(tc, sq.gQ, sq.offQ[m], dstQ, m);        // Q of stage i + 2 first
+        else dma_one(tc, sp.gP, sp.offP[m - 4], dstP, m - 4);      // then P of stage i + 3
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    lds_wait(p[0], q[0]);
+    stores_pending = step_done(i);
+    sq = sp;
+    pb = pn;
+    qb = qn;
+  }
+#undef CCE_READ_FRAGS3
+  wait_dma();   // the surplus loads must have landed before the LDS is reused or released
+}
+
 // Sweep P tiles t0 .. t1-1 (tile t = rows [256 t, 256 t + 256) of P, clamped to p_rows)
 // against one fixed 256-row Q tile, with the K loop running seamlessly from one tile into
 // the next.  After the last stage of each tile, on_tile(t) consumes the accumulators and
-// must leave them zeroed; its return value is that of mma_pipeline's step_done.
-template <int KSTORE = 0, class OnTile>
+// must leave them zeroed; its return value is that of mma_pipeline's step_done.  RING3 selects
+// the five-slice ring (lds must then hold kLdsBytes3 bytes).
+template <int KSTORE = 0, bool RING3 = false, class OnTile>
 __device__ inline void sweep_tiles(const TileCoords& tc, char* lds, const char* P, int p_rows, int64_t ld_bytes,
                                    int t0, int t1, const char* gQ, const uint32_t (&offQ)[4], int KT,
                                    f32x16 (&acc)[kRB][kCB], OnTile on_tile) {
@@ -331,34 +426,34 @@ __device__ inline void sweep_tiles(const TileCoords& tc, char* lds, const char* 
   uint32_t offP[4];
   dma_offsets(tc, min(kTileR, p_rows - t0 * kTileR), ld_bytes, offP);
   int kt = 0, t = t0;   // compute cursor
-  mma_pipeline<false, false, KSTORE>(
-      tc, lds, (t1 - t0) * KT, acc,
-      [&](StageSrc& src) {
-        const int64_t koff = (int64_t)cur_kt * (kTileK * 2);
-        src.gP = gP + koff;
-        src.gQ = gQ + koff;
+  auto next = [&](StageSrc& src) {
+    const int64_t koff = (int64_t)cur_kt * (kTileK * 2);
+    src.gP = gP + koff;
+    src.gQ = gQ + koff;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) { src.offP[j] = offP[j]; src.offQ[j] = offQ[j]; }
-        if (++cur_kt == KT) {
-          if (cur_t + 1 < t1) {
-            cur_kt = 0;
-            ++cur_t;
-            gP += (int64_t)kTileR * ld_bytes;
-            dma_offsets(tc, min(kTileR, p_rows - cur_t * kTileR), ld_bytes, offP);
-          } else {
-            cur_kt = KT - 1;   // past the end: keep re-fetching the last slice (surplus loads)
-          }
-        }
-      },
-      [&](int) {
-        if (++kt == KT) {
-          kt = 0;
-          const bool stored = on_tile(t);
-          ++t;
-          return stored;
-        }
-        return false;
-      });
+    for (int j = 0; j < 4; ++j) { src.offP[j] = offP[j]; src.offQ[j] = offQ[j]; }
+    if (++cur_kt == KT) {
+      if (cur_t + 1 < t1) {
+        cur_kt = 0;
+        ++cur_t;
+        gP += (int64_t)kTileR * ld_bytes;
+        dma_offsets(tc, min(kTileR, p_rows - cur_t * kTileR), ld_bytes, offP);
+      } else {
+        cur_kt = KT - 1;   // past the end: keep re-fetching the last slice (surplus loads)
+      }
+    }
+  };
+  auto step_done = [&](int) {
+    if (++kt == KT) {
+      kt = 0;
+      const bool stored = on_tile(t);
+      ++t;
+      return stored;
+    }
+    return false;
+  };
+  if constexpr (RING3) mma_pipeline3<KSTORE>(tc, lds, (t1 - t0) * KT, acc, next, step_done);
+  else mma_pipeline<false, false, KSTORE>(tc, lds, (t1 - t0) * KT, acc, next, step_done);
 }
 
 // Sweep entries e0 .. e1-1 of a list of independent 256 x 256 tiles, the K loop running
