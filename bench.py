@@ -9,6 +9,9 @@ bound) and the fp64 CPU oracle timed on a bounded sample of the same workload.
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
   python bench.py --sweep      prints a markdown table over the paper's model shapes (Table A3) and
                                batch sizes (Fig. A1 / A2) instead of the JSON line
+  python bench.py --configs    prints a markdown table over the five benchmark configurations (seeded
+                               synthetic data of workloads/): forward, dense / filtered backward, error
+                               of the filtered gradients against the dense ones, extra memory
 """
 import argparse
 import json
@@ -110,6 +113,74 @@ def sweep():
         run("Gemma-2 2B", N, 2304, 256000, 30.0, 3)
 
 
+def configs_table():
+    """The five benchmark configurations on their seeded synthetic data."""
+    import torch
+    import paper_2411_09009_amd as L
+    from workloads import make
+    L.load()
+    dev = torch.device("cuda:0")
+
+    def timed(fn, iters=5):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(iters):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        return sum(ts) / len(ts)
+
+    print("| config | N | D | V | cap | path | fwd ms | fwd % of 2.5 PF | bwd dense ms | bwd dense % | fwd+bwd dense k tok/s "
+          "| bwd filtered ms | blocks kept | filtered + skip-tiles bwd ms | dE / dC filtered vs dense (rel. Frobenius) "
+          "| fwd / bwd workspace MB |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|")
+    for name in ("tiny", "small_vocab", "gemma2_2b", "llama3_8b", "stress", "stress_peaked"):
+        w = make(name)
+        N, D, V = w.N, w.D, w.V
+        if w.dtype == "bf16":
+            E = torch.from_numpy(w.E.view(np.int16)).to(dev).view(torch.bfloat16)
+            C = torch.from_numpy(w.C.view(np.int16)).to(dev).view(torch.bfloat16)
+            code, eps_f = L.CCE_BF16, None
+        else:
+            E, C = torch.from_numpy(w.E).to(dev), torch.from_numpy(w.C).to(dev)
+            code, eps_f = L.CCE_F32, 2.0 ** -12
+        t = torch.from_numpy(w.targets).to(dev)
+        dl = torch.from_numpy(w.mean_dloss()).to(dev)
+        both = L.CCE_FILTER_DE | L.CCE_FILTER_DC
+        o = L.make_opts(code, flags=both | L.CCE_SKIP_TILES)
+        ws = torch.empty(L.cce_workspace_bytes(L.CCE_OP_FORWARD, N, D, V, o), dtype=torch.uint8, device=dev)
+        wb = torch.empty(L.cce_workspace_bytes(L.CCE_OP_BACKWARD, N, D, V, o), dtype=torch.uint8, device=dev)
+        bm = torch.empty(L.cce_block_max_bytes(N, V), dtype=torch.uint8, device=dev)
+        loss, lse = torch.empty(N, device=dev), torch.empty(N, device=dev)
+        dE, dC = torch.empty_like(E), torch.empty_like(C)
+        of = L.make_opts(code, flags=both | L.CCE_SKIP_TILES, workspace=ws, block_max=bm)
+
+        def bwd(eps, flags):
+            ob = L.make_opts(code, flags=flags, filter_eps=eps, workspace=wb, block_max=bm)
+            return lambda: L.cce_backward_ex(E, C, t, lse, dl, w.softcap, w.ignore_index, ob, out_dE=dE, out_dC=dC)
+
+        f = timed(lambda: L.cce_forward_ex(E, C, t, w.softcap, w.ignore_index, of, out_loss=loss, out_lse=lse))
+        b_dense = timed(bwd(0.0, both))
+        rE, rC = dE.float().clone(), dC.float().clone()
+        b_skip = timed(bwd(eps_f, both | L.CCE_SKIP_TILES))
+        b_filt = timed(bwd(eps_f, both))
+        total, kept = L.cce_backward_filter_stats(wb)
+        eE = float((dE.float() - rE).norm() / rE.norm())
+        eC = float((dC.float() - rC).norm() / rC.norm())
+        fl = 2.0 * N * D * V
+        path = "MFMA" if w.dtype == "bf16" else "plain fp32"
+        print("| %s | %d | %d | %d | %g | %s | %.3f | %.1f | %.3f | %.1f | %.0f | %.3f | %d / %d | %.3f | %.1e / %.1e | %.1f / %.0f |"
+              % (name, N, D, V, w.softcap, path, f, fl / f / 1e9 / 25.0, b_dense, 3 * fl / b_dense / 1e9 / 25.0,
+                 N / ((f + b_dense) * 1e-3) / 1e3, b_filt, kept, total, b_skip, eE, eC, ws.numel() / 1e6, wb.numel() / 1e6),
+              flush=True)
+        del E, C, dE, dC, rE, rC, wb, bm
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -119,6 +190,7 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=1536)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", action="store_true")
+    ap.add_argument("--configs", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (how the path would shard is a design note, not code); "
@@ -126,6 +198,9 @@ def main():
         sys.exit(2)
     if args.sweep:
         sweep()
+        return
+    if args.configs:
+        configs_table()
         return
 
     import torch
