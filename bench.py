@@ -303,6 +303,15 @@ def main():
         L.cce_forward_ex(E, C, tg, w.softcap, w.ignore_index, of_rec, out_loss=loss, out_lse=lse)
 
     fwd_rec_ms = timed(fwd_rec)
+    # the same two filtered passes with the larger workspace of CCE_OP_BACKWARD_WIDE (four times
+    # wider vocabulary slabs: fewer launches and fewer passes over the dE accumulator)
+    wide_bytes = L.cce_workspace_bytes(L.CCE_OP_BACKWARD_WIDE, N, D, V, o_s)
+    ws_wide = torch.empty(wide_bytes, dtype=torch.uint8, device=dev)
+    ob_skip_wide = L.make_opts(L.CCE_BF16, flags=both | L.CCE_SKIP_TILES, workspace=ws_wide, block_max=bm)
+    ob_filt_wide = L.make_opts(L.CCE_BF16, workspace=ws_wide)
+    bwd_skip_wide_ms = timed(lambda: bwd(ob_skip_wide))
+    bwd_filt_wide_ms = timed(lambda: bwd(ob_filt_wide))
+    del ws_wide
     bwd_skip_ms = timed(lambda: bwd(ob_skip))
     dE_s, dC_s = dE.clone(), dC.clone()
     bwd_filt_ms = timed(lambda: bwd(ob_filt))
@@ -340,12 +349,15 @@ def main():
         "bwd_dense_tflops": bwd_tflops,
         "frac_mfma_peak_fwd_bwd": (4.0 * fwd_flop / (ms_per_step * 1e-3) / 1e12) / MFMA_BF16_PEAK_TFLOPS,
         "bwd_filtered": {"ms": bwd_filt_ms, "blocks_kept": kept, "blocks_total": total,
-                         "dE_rel_fro_vs_dense": err_dE, "dC_rel_fro_vs_dense": err_dC},
+                         "dE_rel_fro_vs_dense": err_dE, "dC_rel_fro_vs_dense": err_dC,
+                         "ms_wide_workspace": bwd_filt_wide_ms},
         "filtered_skip_tiles": {"fwd_with_record_ms": fwd_rec_ms, "bwd_ms": bwd_skip_ms,
                                 "fwd_bwd_tokens_per_s": N / ((fwd_rec_ms + bwd_skip_ms) * 1e-3),
-                                "record_bytes": bm.numel(), "bit_identical_to_filtered": skip_identical},
+                                "record_bytes": bm.numel(), "bit_identical_to_filtered": skip_identical,
+                                "bwd_ms_wide_workspace": bwd_skip_wide_ms,
+                                "fwd_bwd_tokens_per_s_wide_workspace": N / ((fwd_rec_ms + bwd_skip_wide_ms) * 1e-3)},
         "extra_hbm_bytes": {"forward_workspace": fwd_bytes, "backward_workspace": bwd_bytes,
-                            "logits_avoided_fp32": 4 * N * V},
+                            "backward_workspace_wide": wide_bytes, "logits_avoided_fp32": 4 * N * V},
         "roofline": {"kernel": "fwd_lse_mfma_kernel (timed as cce_forward_ex: + finalize, <1%)",
                      "bound": "mfma", "achieved": fwd_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": fwd_tflops / MFMA_BF16_PEAK_TFLOPS,

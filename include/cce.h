@@ -95,8 +95,13 @@ enum {
 /* cce_workspace_bytes(op, ...) */
 enum {
   CCE_OP_FORWARD = 0,        /* exact requirement of cce_forward_ex */
-  CCE_OP_BACKWARD = 1,       /* recommended size for cce_backward_ex (fastest slab width) */
-  CCE_OP_BACKWARD_MIN = 2    /* smallest size cce_backward_ex accepts (narrowest slab) */
+  CCE_OP_BACKWARD = 1,       /* recommended size for cce_backward_ex: the narrowest slabs at which the
+                                unfiltered pass runs at full speed */
+  CCE_OP_BACKWARD_MIN = 2,   /* smallest size cce_backward_ex accepts (narrowest slab) */
+  CCE_OP_BACKWARD_WIDE = 3   /* largest size cce_backward_ex makes use of: slabs four times as wide.  Each
+                                slab costs one launch per kernel and one pass over the fp32 dE accumulator
+                                whatever the filter leaves of it, so a filtered pass gets faster with fewer,
+                                wider slabs; an unfiltered one does not */
 };
 
 typedef struct cce_opts {
@@ -156,6 +161,8 @@ int cce_forward_ex(const void* E, const void* C, const int64_t* targets,
  * Extra device memory: the workspace: two slabs of the gradient-of-logits matrix
  * (bf16, N x slab width), fp32 [N, D] accumulator(s) and 4 bytes of filter flag per
  * 256 x 64 and 64 x 256 block of logits - the only part that grows with |V|.
+ * Any workspace of at least cce_workspace_bytes(CCE_OP_BACKWARD_MIN) bytes is accepted; the
+ * call uses the widest slab that fits it, up to that of CCE_OP_BACKWARD_WIDE.
  * Work that the call spreads over the library's helper streams is joined back into
  * opts->stream before it returns; the whole call can be captured into a HIP graph.
  *

@@ -35,6 +35,7 @@ constexpr int64_t kMfmaSlabCols = 6144;  // recommended backward slab width (voc
 constexpr int64_t kPlainSlabCols = 4096;
 constexpr int kMaxFilteredKSteps = 2048;
 constexpr int kSlabBuffers = 2;          // vocabulary slabs in flight in the MFMA backward pass
+constexpr int64_t kWideSlabFactor = 4;   // CCE_OP_BACKWARD_WIDE: slab width over the recommended one
 
 int cu_count() {
   static int cached[kMaxDevices] = {};
@@ -302,10 +303,27 @@ int64_t recommended_slab(bool mfma, int64_t N, int64_t V) {
   return full < rec ? full : rec;
 }
 
-// widest slab (multiple of the tile width, at most the recommended one) that fits `bytes`
+// Widest slab a larger workspace buys (CCE_OP_BACKWARD_WIDE).  Every slab costs one launch of each
+// kernel and one read-modify-write pass over the dE accumulator whatever it contains, which is what
+// a filtered pass mostly consists of; fewer, wider slabs cut exactly that.  Bounded by the 32-bit
+// element offsets of the recompute kernel and by the step list a filtered dE product keeps in LDS.
+int64_t widest_slab(bool mfma, int64_t N, int64_t V) {
+  const int64_t rec = recommended_slab(mfma, N, V);
+  if (!mfma) return rec;
+  int64_t wide = rec * kWideSlabFactor;
+  const int64_t by_offsets = (((int64_t)1 << 30) / round_up(N, 256)) / 256 * 256;
+  const int64_t by_steps = (int64_t)kMaxFilteredKSteps * 64;
+  if (wide > by_offsets) wide = by_offsets;
+  if (wide > by_steps) wide = by_steps;
+  const int64_t full = round_up(V, 256);
+  if (wide > full) wide = full;
+  return wide > rec ? wide : rec;
+}
+
+// widest slab (multiple of the tile width, at most the widest one above) that fits `bytes`
 int64_t fit_slab(bool mfma, int64_t N, int64_t D, int64_t V, size_t bytes, bool sort, bool lists, bool compact) {
   const int64_t t = slab_tile(mfma);
-  int64_t lo = 0, hi = recommended_slab(mfma, N, V) / t;   // in tiles
+  int64_t lo = 0, hi = widest_slab(mfma, N, V) / t;   // in tiles
   if (mfma) {
     // the recompute kernel addresses the slab with 32-bit element offsets
     const int64_t cap = (((int64_t)1 << 30) / round_up(N, 256)) / t;
@@ -356,6 +374,8 @@ size_t cce_workspace_bytes(int op, int64_t N, int64_t D, int64_t V, const cce_op
     case CCE_OP_BACKWARD:
       return layout_backward(mfma, N, D, V, recommended_slab(mfma, N, V), sort, lists, compact).total_bytes;
     case CCE_OP_BACKWARD_MIN: return layout_backward(mfma, N, D, V, slab_tile(mfma), sort, lists, compact).total_bytes;
+    case CCE_OP_BACKWARD_WIDE:
+      return layout_backward(mfma, N, D, V, widest_slab(mfma, N, V), sort, lists, compact).total_bytes;
     default: return 0;
   }
 }

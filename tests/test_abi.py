@@ -67,6 +67,15 @@ def test_backward_workspace_is_bounded_by_the_slab_not_the_vocabulary():
     # the only |V|-dependent part is one 4-byte filter flag per 256 x 64 and per 64 x 256 block of logits
     assert 0 <= rec2 - rec <= N * (1024000 - 256000) // 2048 + 4096 and 0 < mn < rec
     assert rec < N * 256000 * 2 / 5        # far below even a bf16 logit matrix
+    # a larger workspace buys slabs up to four times as wide, never more
+    wide = L.cce_workspace_bytes(L.CCE_OP_BACKWARD_WIDE, N, D, 256000, o)
+    assert rec < wide <= 4 * rec
+    # small vocabulary: one slab already holds all of it, so there is nothing to widen
+    assert (L.cce_workspace_bytes(L.CCE_OP_BACKWARD_WIDE, N, D, 4096, o)
+            == L.cce_workspace_bytes(L.CCE_OP_BACKWARD, N, D, 4096, o))
+    # the widest slab stays addressable with 32-bit element offsets at the largest benchmark shape
+    big = L.cce_workspace_bytes(L.CCE_OP_BACKWARD_WIDE, 65536, 5120, 131072, o)
+    assert big <= 65536 * 5120 * 4 + 2 * 2 * 2 ** 30 + 64 * 2 ** 20
     assert L.cce_workspace_bytes(99, N, D, 256000, o) == 0
     assert L.cce_workspace_bytes(L.CCE_OP_FORWARD, 0, D, 256000, o) == 0
 

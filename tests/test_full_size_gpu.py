@@ -91,6 +91,14 @@ def test_full_size_matches_stored_oracle(cce, name):
     assert fE <= elemE + eE + 1e-3 and fC <= elemC + eC + 1e-3
     assert 0 < stats_f[1] <= stats_f[0]
 
+    print("backward (filtered, wide slabs) %s" % name, flush=True)
+    dEw, dCw, stats_w = run_backward(w, E, C, t, lse, dloss, op=L.CCE_OP_BACKWARD_WIDE)
+    wE, wC = rel_fro(rows_of(dEw, er), ref_dE), rel_fro(rows_of(dCw, vr), ref_dC)
+    print("  wide:     dE rows err %.2e  dC rows err %.2e" % (wE, wC), flush=True)
+    assert wE <= elemE + eE + 1e-3 and wC <= elemC + eC + 1e-3
+    assert stats_w == stats_f and torch.equal(dCw, dCf)
+    del dEw, dCw
+
     print("backward (filtered, vocabulary sorted) %s" % name, flush=True)
     flags = L.CCE_FILTER_DE | L.CCE_FILTER_DC | L.CCE_VOCAB_SORT
     dEs, dCs, stats_s = run_backward(w, E, C, t, lse, dloss, flags=flags)

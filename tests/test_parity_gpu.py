@@ -275,6 +275,31 @@ def test_narrow_slabs_and_small_workspace(cce):
     assert ei.value.status == -2
 
 
+def test_wide_slabs_with_a_larger_workspace(cce):
+    """A workspace of CCE_OP_BACKWARD_WIDE bytes gives fewer, wider slabs and the same gradients."""
+    w = make("gemma2_2b", N=4400, D=64, V=30000)
+    o = L.make_opts(L.CCE_BF16)
+    rec = L.cce_workspace_bytes(L.CCE_OP_BACKWARD, w.N, w.D, w.V, o)
+    wide = L.cce_workspace_bytes(L.CCE_OP_BACKWARD_WIDE, w.N, w.D, w.V, o)
+    assert wide > 2 * rec
+    E, C, t = to_device(w)
+    _, lse = run_forward(w, E, C, t)
+    dloss = torch.from_numpy(w.mean_dloss()).cuda()
+    _, _, rdE, rdC = oracle_all(w)
+    dE, dC, _ = run_backward(w, E, C, t, lse, dloss, eps=0.0)
+    dE2, dC2, _ = run_backward(w, E, C, t, lse, dloss, eps=0.0, op=L.CCE_OP_BACKWARD_WIDE)
+    assert rel_fro(f64(dE2), rdE) <= TOL_GRAD and rel_fro(f64(dC2), rdC) <= TOL_GRAD
+    assert torch.equal(dC, dC2)
+    # more than the widest slab needs is accepted and changes nothing further
+    dE3, dC3, _ = run_backward(w, E, C, t, lse, dloss, eps=0.0, ws_bytes=wide + (64 << 20))
+    assert torch.equal(dE2, dE3) and torch.equal(dC2, dC3)
+    # filtered: the same blocks are kept whatever the slab width
+    dEf, dCf, st = run_backward(w, E, C, t, lse, dloss)
+    dEf2, dCf2, st2 = run_backward(w, E, C, t, lse, dloss, op=L.CCE_OP_BACKWARD_WIDE)
+    assert st == st2 and torch.equal(dCf, dCf2)
+    assert rel_fro(f64(dEf2), f64(dEf)) <= 1e-2
+
+
 def test_edge_cases(cce):
     # all tokens ignored: loss 0, gradients 0
     w = make("gemma2_2b", N=260, D=64, V=300, ignore_frac=1.0)
