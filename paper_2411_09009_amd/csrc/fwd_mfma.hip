@@ -155,7 +155,7 @@ __global__ __launch_bounds__(kThreads) void fwd_lse_mfma_kernel(FwdMfmaParams p)
   const float cap_scale = MODE != kNoCap ? 2.f * kLog2e / p.softcap : 0.f;   // exp(2z/cap) = 2^(z*cap_scale)
   const float cap_l2 = MODE != kNoCap ? p.softcap * kLog2e : kLog2e;
 
-  sweep_tiles<REC ? 2 : 0, true>(tc, lds, (const char*)p.C, p.V, ld_bytes, vt0, vt1, gQ, offQ, KT, acc, [&](int vt) {
+  sweep_tiles<REC ? 2 : 0, true, true>(tc, lds, (const char*)p.C, p.V, ld_bytes, vt0, vt1, gQ, offQ, KT, acc, [&](int vt) {
     // fold the finished logit tile into the running (max, sum)
     const int v_base = vt * kTileR + tc.wave_r * kWaveRows;
     float amax2[kCB] = {-INFINITY, -INFINITY};
