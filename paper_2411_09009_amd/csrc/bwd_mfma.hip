@@ -19,6 +19,8 @@
 #include "kernels.h"
 #include "mfma_tile.h"
 
+#include <type_traits>
+
 namespace cce {
 
 namespace {
@@ -81,6 +83,8 @@ __global__ __launch_bounds__(256) void tile_compact_kernel(TileListParams p) {
 }
 
 enum { kNoCap = 0, kCap = 1 };
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 constexpr int kMaxKSteps = 2048;   // longest filtered contraction: 131072 / 64
 
 // ------------------------------------------------------------------ recompute + G
@@ -127,7 +131,9 @@ __global__ __launch_bounds__(kThreads) void bwd_recompute_mfma_kernel(BwdCommon 
     for (int cb = 0; cb < kCB; ++cb) {
       const int n = n0 + tc.wave_c * kWaveCols + cb * 32 + (tc.lane & 31);
       ncol[cb] = n;
-      lse2[cb] = 0.f;
+      // a token that takes no part (ignored, target out of range, past N): with lse = +inf every
+      // 2^(a - lse) of its column is exactly 0, so its column of G needs no masking below
+      lse2[cb] = INFINITY;
       lam[cb] = 0.f;
       tgt[cb] = -1;
       if (n < c.N) {
@@ -170,66 +176,96 @@ __global__ __launch_bounds__(kThreads) void bwd_recompute_mfma_kernel(BwdCommon 
   // read side: instruction rr covers rows rr * 8 + lane / 8, logical chunk lane % 8
   const uint32_t rd_row = (uint32_t)(tc.lane >> 3), rd_chunk = (uint32_t)(tc.lane & 7);
 
-  auto epilogue = [&](int t) {
-    const int vl_base = t * kTileR + tc.wave_r * kWaveRows;   // slab-local vocabulary row of this wave
-    bool sig[2] = {false, false};                              // halves rb {0,1} and {2,3}
+  // G and GZ of one of the lane's two token columns (cb): 4 blocks x 16 rows.  Straight-line
+  // code: the 64 elements are independent chains the scheduler interleaves.  CAREFUL adds what
+  // few column blocks need: the onehot term (a target inside the wave's 128 rows) and the mask of
+  // rows past |V| (last vocabulary tile).  gmax[h] collects max |G| over rows h * 64 .. h * 64 + 63.
+  auto column = [&](auto careful_tag, int cb, int vl_base, float (&gmax)[2]) {
+    constexpr bool CAREFUL = decltype(careful_tag)::value;
+    const float l2 = lse2[cb], lm = lam[cb];
+    const int tg = tgt[cb];
 #pragma unroll
-    for (int cb = 0; cb < kCB; ++cb) {
-      const bool tok = tgt[cb] >= 0;
+    for (int rbp = 0; rbp < 2; ++rbp) {
 #pragma unroll
-      for (int rbp = 0; rbp < 2; ++rbp) {
+      for (int rbl = 0; rbl < 2; ++rbl) {
+        const int rb = rbp * 2 + rbl;
 #pragma unroll
-        for (int rbl = 0; rbl < 2; ++rbl) {
-          const int rb = rbp * 2 + rbl;
+        for (int g = 0; g < 4; ++g) {
+          float gz[4];
+          const int v = sl.v0 + vl_base + rb * 32 + 8 * g + 4 * (tc.lane >> 5);
 #pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            bf16 o[4];
-            const int vl = vl_base + rb * 32 + 8 * g + 4 * (tc.lane >> 5);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-              const float z = acc[rb][cb][g * 4 + j];
-              acc[rb][cb][g * 4 + j] = 0.f;
-              float a2, dcap;
-              if (MODE == kCap) {
-                float e = __builtin_amdgcn_exp2f(z * cap_scale);
-                float r = __builtin_amdgcn_rcpf(1.f + e);
-                float th = fmaf(-2.f, r, 1.f);           // tanh(z / cap)
-                a2 = cap_l2 * th;
-                dcap = fmaf(-th, th, 1.f);
-              } else {
-                a2 = z * kLog2e;
-                dcap = 1.f;
-              }
-              const int v = sl.v0 + vl + j;
-              float gval = __builtin_amdgcn_exp2f(a2 - lse2[cb]) - (v == tgt[cb] ? 1.f : 0.f);
-              const bool live = tok && v < c.V;
-              sig[rbp] |= live && fabsf(gval) >= eps;
-              float gz = live ? lam[cb] * gval * dcap : 0.f;
-              o[j] = (bf16)gz;
+          for (int j = 0; j < 4; ++j) {
+            const float z = acc[rb][cb][g * 4 + j];
+            acc[rb][cb][g * 4 + j] = 0.f;
+            float x, dcap;
+            if (MODE == kCap) {
+              const float e = __builtin_amdgcn_exp2f(z * cap_scale);
+              const float r = __builtin_amdgcn_rcpf(1.f + e);
+              const float th = fmaf(-2.f, r, 1.f);           // tanh(z / cap)
+              x = fmaf(cap_l2, th, -l2);
+              dcap = fmaf(-th, th, 1.f);
+            } else {
+              x = fmaf(z, kLog2e, -l2);
+              dcap = 1.f;
             }
-            uint2 packed;
-            __builtin_memcpy(&packed, o, 8);
-            // staging row = token (lane & 31), 16-byte chunk = rbl * 4 + g, half = lane >> 5
-            const uint32_t wa = st_wr + ((((uint32_t)(rbl * 4 + g)) ^ st_wswz) << 4);
-            asm volatile("ds_write_b64 %0, %1" ::"v"(wa), "v"(packed));
+            float gval = __builtin_amdgcn_exp2f(x);
+            if (CAREFUL) {
+              gval -= (v + j == tg) ? 1.f : 0.f;
+              // rows past |V|: cleared by a bit mask, which keeps the arithmetic above unconditional
+              const uint32_t keep = (v + j < c.V) ? 0xffffffffu : 0u;
+              gval = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, gval) & keep);
+            }
+            gmax[rbp] = fmaxf(gmax[rbp], fabsf(gval));
+            gz[j] = MODE == kCap ? lm * gval * dcap : lm * gval;
           }
-        }
-        // 32 tokens x 64 vocabulary entries are staged: write them out, 128 contiguous bytes per token
-#pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-          const uint32_t row = (uint32_t)rr * 8u + rd_row;
-          const uint32_t ra = stage_base + row * 128u + ((rd_chunk ^ ((row >> 1) & 7u)) << 4);
-          uint4 val;
-          asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(val) : "v"(ra));
-          // token of this staging row: same wave column block, row-th of the 32 tokens of cb.
-          // The address is derived from an opaque copy so that it is computed here and not
-          // hoisted out of the tile loop into registers that stay live across the MFMA stages.
-          uint32_t tok_row = (uint32_t)(n0 + tc.wave_c * kWaveCols + cb * 32) + row;
-          asm volatile("" : "+v"(tok_row));
-          bf16* dst = sl.GZ + ((size_t)tok_row * (uint32_t)sl.vs + (uint32_t)(vl_base + rbp * 64) + rd_chunk * 8u);
-          *(uint4*)dst = val;
+          f32x2 lo = {gz[0], gz[1]}, hi = {gz[2], gz[3]};
+          bf16x2 blo = __builtin_convertvector(lo, bf16x2), bhi = __builtin_convertvector(hi, bf16x2);
+          uint2 packed;
+          packed.x = __builtin_bit_cast(uint32_t, blo);
+          packed.y = __builtin_bit_cast(uint32_t, bhi);
+          // staging row = token (lane & 31), 16-byte chunk = rbl * 4 + g, half = lane >> 5
+          const uint32_t wa = st_wr + ((((uint32_t)(rbl * 4 + g)) ^ st_wswz) << 4);
+          asm volatile("ds_write_b64 %0, %1" ::"v"(wa), "v"(packed));
         }
       }
+      // 32 tokens x 64 vocabulary entries are staged: write them out, 128 contiguous bytes per token
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
+        const uint32_t row = (uint32_t)rr * 8u + rd_row;
+        const uint32_t ra = stage_base + row * 128u + ((rd_chunk ^ ((row >> 1) & 7u)) << 4);
+        uint4 val;
+        asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(val) : "v"(ra));
+        // token of this staging row: same wave column block, row-th of the 32 tokens of cb.
+        // The address is derived from an opaque copy so that it is computed here and not
+        // hoisted out of the tile loop into registers that stay live across the MFMA stages.
+        uint32_t tok_row = (uint32_t)(n0 + tc.wave_c * kWaveCols + cb * 32) + row;
+        asm volatile("" : "+v"(tok_row));
+        bf16* dst = sl.GZ + ((size_t)tok_row * (uint32_t)sl.vs + (uint32_t)(vl_base + rbp * 64) + rd_chunk * 8u);
+        *(uint4*)dst = val;
+      }
+    }
+  };
+
+  auto epilogue = [&](int t) {
+    const int vl_base = t * kTileR + tc.wave_r * kWaveRows;   // slab-local vocabulary row of this wave
+    const int v_wave = sl.v0 + vl_base;
+    const bool ragged = v_wave + kWaveRows > c.V;              // wave-uniform
+    float gmax[2] = {0.f, 0.f};                                // halves rb {0,1} and {2,3}
+#pragma unroll
+    for (int cb = 0; cb < kCB; ++cb) {
+      const bool target_here = (uint32_t)(tgt[cb] - v_wave) < (uint32_t)kWaveRows;
+      if (ragged || __builtin_amdgcn_ballot_w64(target_here) != 0) column(std::true_type{}, cb, vl_base, gmax);
+      else column(std::false_type{}, cb, vl_base, gmax);
+    }
+    bool sig[2];
+    if (eps > 0.f) {
+      sig[0] = gmax[0] >= eps;
+      sig[1] = gmax[1] >= eps;
+    } else {
+      // filter off: a block counts as kept when it holds an element of a token that takes part
+      const bool tok = tgt[0] >= 0 || tgt[1] >= 0;
+      sig[0] = tok && v_wave < c.V;
+      sig[1] = tok && v_wave + 64 < c.V;
     }
     // block flags for the gradient filter (an OR, so the order of arrival is immaterial)
     const bool any0 = __builtin_amdgcn_ballot_w64(sig[0]) != 0;

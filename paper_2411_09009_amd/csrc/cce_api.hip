@@ -5,6 +5,7 @@
 #include "kernels.h"
 
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -38,15 +39,15 @@ constexpr int kSlabBuffers = 2;          // vocabulary slabs in flight in the MF
 constexpr int64_t kWideSlabFactor = 4;   // CCE_OP_BACKWARD_WIDE: slab width over the recommended one
 
 int cu_count() {
-  static int cached[kMaxDevices] = {};
+  static std::atomic<int> cached[kMaxDevices];   // zero-initialised; 0 = not asked yet
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
-  if (cached[dev] == 0) {
-    int n = 0;
+  int n = cached[dev].load(std::memory_order_relaxed);
+  if (n == 0) {
     if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-    cached[dev] = n;
+    cached[dev].store(n, std::memory_order_relaxed);   // every thread computes the same value
   }
-  return cached[dev];
+  return n;
 }
 
 // Library-owned workspace for the plain entry points: one buffer per device,
@@ -356,7 +357,7 @@ const char* cce_strerror(int status) {
     case CCE_OK: return "success";
     case CCE_EINVAL: return "invalid argument (null or misaligned pointer, non-positive size, bad softcap or eps)";
     case CCE_EWORKSPACE: return "workspace missing or too small (see cce_workspace_bytes)";
-    case CCE_EUNSUPPORTED: return "unsupported dtype or flag";
+    case CCE_EUNSUPPORTED: return "unsupported dtype, flag combination, or a size beyond the kernels' 32-bit offsets";
     case CCE_EHIP: return g_hip_error;
     default: return "unknown status";
   }
@@ -489,13 +490,14 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
   c.filter_dE = (opts->flags & CCE_FILTER_DE) ? 1 : 0;
   c.filter_dC = (opts->flags & CCE_FILTER_DC) ? 1 : 0;
   c.stats = (FilterStats*)ws;
+  // the MFMA gradient products address E and a slab of C with 32-bit byte offsets
+  if (mfma &&
+      ((uint64_t)N * (uint64_t)D * 2 >= ((uint64_t)1 << 32) || (uint64_t)vs * (uint64_t)D * 2 >= ((uint64_t)1 << 32)))
+    return CCE_EUNSUPPORTED;
   CCE_HIP(launch_clear_stats(c.stats, stream));
   float* dEacc = (float*)(ws + plan.off_dEacc);
 
   if (mfma) {
-    // the gradient products address E and a slab of C with 32-bit byte offsets
-    if ((uint64_t)N * (uint64_t)D * 2 >= ((uint64_t)1 << 32) || (uint64_t)vs * (uint64_t)D * 2 >= ((uint64_t)1 << 32))
-      return CCE_EUNSUPPORTED;
     Helpers* h = nullptr;
     st = helpers_for_device(&h);
     if (st != CCE_OK) return st;
