@@ -416,34 +416,62 @@ __global__ __launch_bounds__(kThreads) void bwd_product_mfma_kernel(BwdCommon c,
       out_row[cb] = (sl.perm && vv < c.V) ? sl.perm[vv] : vv;
     }
   }
+  // D is a multiple of 64, so each of the wave's four 32-row blocks lies inside D or outside as a whole
+  const int d_wave = d0 + tc.wave_r * kWaveRows;
+  const int rb_valid = (c.D - d_wave) / 32;   // blocks inside D (may be <= 0 or > kRB)
 #pragma unroll
   for (int cb = 0; cb < kCB; ++cb) {
     const int col = c0 + tc.wave_c * kWaveCols + cb * 32 + (tc.lane & 31);
+    if (DC) {
+      if (sl.v0 + col < c.V) {
+        bf16* row = out_dC + (int64_t)out_row[cb] * c.D + d_wave + 4 * (tc.lane >> 5);
 #pragma unroll
-    for (int rb = 0; rb < kRB; ++rb)
+        for (int rb = 0; rb < kRB; ++rb)
+          if (rb < rb_valid) {
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int d = d0 + tc.wave_r * kWaveRows + rb * 32 + 8 * g + 4 * (tc.lane >> 5);
-        if (d >= c.D) continue;
-        float4 v = make_float4(acc[rb][cb][g * 4 + 0], acc[rb][cb][g * 4 + 1], acc[rb][cb][g * 4 + 2],
-                               acc[rb][cb][g * 4 + 3]);
-        if (DC) {
-          const int vv = sl.v0 + col;
-          if (vv < c.V) {
-            bf16 o[4] = {(bf16)v.x, (bf16)v.y, (bf16)v.z, (bf16)v.w};
-            uint2 packed;
-            __builtin_memcpy(&packed, o, 8);
-            *(uint2*)(out_dC + (int64_t)out_row[cb] * c.D + d) = packed;
+            for (int g = 0; g < 4; ++g) {
+              f32x2 lo = {acc[rb][cb][g * 4 + 0], acc[rb][cb][g * 4 + 1]};
+              f32x2 hi = {acc[rb][cb][g * 4 + 2], acc[rb][cb][g * 4 + 3]};
+              uint2 packed;
+              packed.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
+              packed.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
+              *(uint2*)(row + rb * 32 + 8 * g) = packed;
+            }
           }
-        } else if (col < c.N) {
-          float4* dst = (float4*)(sl.dEacc + (int64_t)part * sl.dE_part_stride + (int64_t)col * c.D + d);
-          if (!sl.first) {
-            float4 old = *dst;
-            v.x += old.x; v.y += old.y; v.z += old.z; v.w += old.w;
-          }
-          *dst = v;
-        }
       }
+    } else if (col < c.N) {
+      float* row = sl.dEacc + (int64_t)part * sl.dE_part_stride + (int64_t)col * c.D + d_wave + 4 * (tc.lane >> 5);
+      if (!sl.first) {
+        // every read of the column is issued before the first is waited for: 16 loads in
+        // flight instead of one round trip to memory after the other
+        float4 old[kRB][4];
+#pragma unroll
+        for (int rb = 0; rb < kRB; ++rb)
+          if (rb < rb_valid) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) old[rb][g] = *(const float4*)(row + rb * 32 + 8 * g);
+          }
+#pragma unroll
+        for (int rb = 0; rb < kRB; ++rb)
+          if (rb < rb_valid) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+              acc[rb][cb][g * 4 + 0] += old[rb][g].x;
+              acc[rb][cb][g * 4 + 1] += old[rb][g].y;
+              acc[rb][cb][g * 4 + 2] += old[rb][g].z;
+              acc[rb][cb][g * 4 + 3] += old[rb][g].w;
+            }
+          }
+      }
+#pragma unroll
+      for (int rb = 0; rb < kRB; ++rb)
+        if (rb < rb_valid) {
+#pragma unroll
+          for (int g = 0; g < 4; ++g)
+            *(float4*)(row + rb * 32 + 8 * g) = make_float4(acc[rb][cb][g * 4 + 0], acc[rb][cb][g * 4 + 1],
+                                                            acc[rb][cb][g * 4 + 2], acc[rb][cb][g * 4 + 3]);
+        }
+    }
   }
 }
 
