@@ -228,20 +228,26 @@ __global__ __launch_bounds__(kThreads) void bwd_recompute_mfma_kernel(BwdCommon 
           asm volatile("ds_write_b64 %0, %1" ::"v"(wa), "v"(packed));
         }
       }
-      // 32 tokens x 64 vocabulary entries are staged: write them out, 128 contiguous bytes per token
+      // 32 tokens x 64 vocabulary entries are staged: write them out, 128 contiguous bytes per token.
+      // Instruction rr covers staging rows rr * 8 + lane / 8; the four reads are issued together
+      // and waited for once.
+      u32x4 val[4];
 #pragma unroll
       for (int rr = 0; rr < 4; ++rr) {
         const uint32_t row = (uint32_t)rr * 8u + rd_row;
         const uint32_t ra = stage_base + row * 128u + ((rd_chunk ^ ((row >> 1) & 7u)) << 4);
-        uint4 val;
-        asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(val) : "v"(ra));
+        asm volatile("ds_read_b128 %0, %1" : "=v"(val[rr]) : "v"(ra));
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(val[0]), "+v"(val[1]), "+v"(val[2]), "+v"(val[3]));
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
         // token of this staging row: same wave column block, row-th of the 32 tokens of cb.
         // The address is derived from an opaque copy so that it is computed here and not
         // hoisted out of the tile loop into registers that stay live across the MFMA stages.
-        uint32_t tok_row = (uint32_t)(n0 + tc.wave_c * kWaveCols + cb * 32) + row;
+        uint32_t tok_row = (uint32_t)(n0 + tc.wave_c * kWaveCols + cb * 32) + (uint32_t)rr * 8u + rd_row;
         asm volatile("" : "+v"(tok_row));
         bf16* dst = sl.GZ + ((size_t)tok_row * (uint32_t)sl.vs + (uint32_t)(vl_base + rbp * 64) + rd_chunk * 8u);
-        *(uint4*)dst = val;
+        *(u32x4*)dst = val[rr];
       }
     }
   };
