@@ -414,14 +414,14 @@ __device__ inline void mma_pipeline3(const TileCoords& tc, char* lds, int nsteps
 // against one fixed 256-row Q tile, with the K loop running seamlessly from one tile into
 // the next.  After the last stage of each tile, on_tile(t) consumes the accumulators and
 // must leave them zeroed; its return value is that of mma_pipeline's step_done.  RING3 selects
-// the five-slice ring (lds must then hold kLdsBytes3 bytes).  With SERPENTINE, tiles with odd t
+// the five-slice ring (lds must then hold kLdsBytes3 bytes).  With `serpentine`, tiles with odd t
 // take their 64-deep K stages in descending order: the Q slices such a tile starts with are the
 // ones the tile before it has just used, still in the L2 (a third less traffic behind the L2 in
 // the forward pass).  The sum over K of an element then depends on the parity of its tile.
-template <int KSTORE = 0, bool RING3 = false, bool SERPENTINE = false, class OnTile>
+template <int KSTORE = 0, bool RING3 = false, class OnTile>
 __device__ inline void sweep_tiles(const TileCoords& tc, char* lds, const char* P, int p_rows, int64_t ld_bytes,
                                    int t0, int t1, const char* gQ, const uint32_t (&offQ)[4], int KT,
-                                   f32x16 (&acc)[kRB][kCB], OnTile on_tile) {
+                                   f32x16 (&acc)[kRB][kCB], OnTile on_tile, bool serpentine = false) {
   if (t0 >= t1) return;
   // DMA cursor: (tile, k-step) of the next stage to fetch
   int cur_t = t0, cur_kt = 0;
@@ -430,7 +430,7 @@ __device__ inline void sweep_tiles(const TileCoords& tc, char* lds, const char* 
   dma_offsets(tc, min(kTileR, p_rows - t0 * kTileR), ld_bytes, offP);
   int kt = 0, t = t0;   // compute cursor
   auto next = [&](StageSrc& src) {
-    const int64_t koff = (int64_t)((SERPENTINE && (cur_t & 1)) ? KT - 1 - cur_kt : cur_kt) * (kTileK * 2);
+    const int64_t koff = (int64_t)((serpentine && (cur_t & 1)) ? KT - 1 - cur_kt : cur_kt) * (kTileK * 2);
     src.gP = gP + koff;
     src.gQ = gQ + koff;
 #pragma unroll
