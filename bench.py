@@ -30,8 +30,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16, vendor figure (no sparsi
 # HBM bytes one launch of fwd_lse_mfma_kernel moves at the Gemma-2-2B shape, from the
 # rocprofv3 --pmc runs summarised in profiles/bench_gemma2_2b_hbm_traffic.md
 # (FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter reads for
-# cce_probe_copy of 1 GiB).  None for other workloads.
-MEASURED_FWD_TRAFFIC_BYTES = {"gemma2_2b": 19937.5e6 + 134.3e6}
+# cce_probe_copy of 1 GiB; median over the launches, the first, cold one reads more).
+# None for other workloads.
+MEASURED_FWD_TRAFFIC_BYTES = {"gemma2_2b": 12397.2e6 + 0.5e6}
 
 
 def cpu_baseline(w, rows):
