@@ -14,3 +14,4 @@ from .binding import (  # noqa: F401
     cce_forward, cce_forward_ex, cce_backward, cce_backward_ex, cce_backward_filter_stats,
     make_opts, cce_probe_mfma, cce_probe_copy,
 )
+from .autograd import linear_cross_entropy  # noqa: F401
