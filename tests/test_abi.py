@@ -127,3 +127,25 @@ def test_product_package_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.replace("no CPU or eager", ""), (f, "mentions the oracle")
+
+
+def test_header_is_plain_c_and_the_library_links_from_c(tmp_path):
+    """include/cce.h is C99 (no C++ needed), and a C program linked against libcce.so can call it."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    L.load()
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    inc = os.path.join(root, "include")
+    for h in sorted(os.listdir(inc)):
+        subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-x", "c",
+                        os.path.join(inc, h)], check=True)
+    libdir = os.path.dirname(L.LIB_PATH)
+    exe = str(tmp_path / "use_from_c")
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Werror", "-I", inc, os.path.join(root, "tests", "abi_c", "use_from_c.c"),
+                    "-L", libdir, "-lcce", "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib", "-o", exe], check=True)
+    r = subprocess.run([exe], stdout=subprocess.PIPE, text=True)
+    assert r.returncode == 0, r.stdout
+    assert r.stdout.startswith("forward ")
