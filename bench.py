@@ -34,6 +34,15 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16, vendor figure (no sparsi
 # None for other workloads.
 MEASURED_FWD_TRAFFIC_BYTES = {"gemma2_2b": 12397.2e6 + 0.5e6}
 
+# The paper's own figures for this shape (Table 1 and its ablation rows: one A100-SXM4-80GB, real
+# Gemma-2 2B weights, Alpaca tokens, N = 8192; forward / backward / both in ms).  Another machine and
+# another kernel technology: context for the numbers printed here, not their target.  vs_baseline divides
+# by the paper's headline row (filter and vocabulary sorting on, 145 ms), although the timed step here has
+# the filter off: the conservative reading.  The like-for-like row for a dense pass, which does not
+# depend on the data, is "no gradient filter" (357 ms); both ratios are in paper_context.
+PAPER_GEMMA2_2B_MS = {"cce": (46.0, 100.0, 145.0), "cce_no_gradient_filter": (45.0, 314.0, 357.0),
+                      "cce_no_vocab_sorting": (45.0, 115.0, 159.0)}
+
 
 def cpu_baseline(w, rows):
     """The oracle as it stands, forward + backward, on the first `rows` tokens."""
@@ -326,6 +335,22 @@ def main():
     err_dC = float((dC_f - dC.float()).norm() / dC.float().norm())
     del dE_f, dC_f
 
+    paper_context = None
+    vs_baseline = None
+    if w.spec.name == "gemma2_2b" and (N, D, V) == (8192, 2304, 256000):
+        dense_paper = N / (PAPER_GEMMA2_2B_MS["cce_no_gradient_filter"][2] * 1e-3)
+        best_paper = N / (PAPER_GEMMA2_2B_MS["cce"][2] * 1e-3)
+        vs_baseline = (N / (ms_per_step * 1e-3)) / best_paper
+        paper_context = {
+            "hardware": "1x NVIDIA A100-SXM4-80GB (paper Table 1), real Gemma-2 2B weights and Alpaca tokens",
+            "fwd_bwd_fwdbwd_ms": PAPER_GEMMA2_2B_MS,
+            "tokens_per_s_fwd_bwd_no_gradient_filter": dense_paper,
+            "tokens_per_s_fwd_bwd_filtered_and_sorted": best_paper,
+            "vs_baseline_is": "value (dense backward, this machine) / tokens_per_s_fwd_bwd_filtered_and_sorted",
+            "dense_vs_dense": (N / (ms_per_step * 1e-3)) / dense_paper,
+            "this_run_filtered_tokens_per_s": N / ((fwd_ms + bwd_filt_ms) * 1e-3),
+        }
+
     fwd_flop = 2.0 * N * D * V
     fwd_tflops = fwd_flop / (fwd_ms * 1e-3) / 1e12
     bwd_tflops = 3.0 * fwd_flop / (bwd_ms * 1e-3) / 1e12
@@ -339,7 +364,7 @@ def main():
         "ms_per_step": ms_per_step,
         "higher_is_better": True,
         "scaling": "weak",
-        "vs_baseline": None,
+        "vs_baseline": vs_baseline,
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": "%s N=%d D=%d V=%d softcap=%g" % (w.spec.name, N, D, V, w.softcap),
@@ -371,6 +396,8 @@ def main():
                                     "unit": "TFLOP/s", "frac": bwd_tflops / MFMA_BF16_PEAK_TFLOPS,
                                     "algorithmic_flop_per_call": 3.0 * fwd_flop},
     }
+    if paper_context is not None:
+        out["paper_context"] = paper_context
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, min(args.cpu_rows, N))
     print(json.dumps(out))
