@@ -48,7 +48,9 @@ typedef enum cce_status {
   CCE_EWORKSPACE = -2,   /* opts->workspace missing or smaller than the minimum */
   CCE_EUNSUPPORTED = -3, /* unknown dtype or flag, or a size beyond the kernels' 32-bit offsets
                             (backward on the MFMA path: N * D * 2 bytes must stay below 4 GiB) */
-  CCE_EHIP = -4          /* a HIP runtime call failed; see cce_strerror */
+  CCE_EHIP = -4,         /* a HIP runtime call failed; see cce_strerror */
+  CCE_ESCRATCH = -5      /* cce_forward_noalloc: the problem needs more scratch than the library's static
+                            array holds (cce_noalloc_scratch_bytes); cce_strerror gives both figures */
 } cce_status;
 
 enum { CCE_BF16 = 0, CCE_F32 = 1 };
@@ -144,6 +146,29 @@ int cce_forward_ex(const void* E, const void* C, const int64_t* targets,
                    int64_t N, int64_t D, int64_t V,
                    float softcap, int64_t ignore_index,
                    float* out_loss, float* out_lse, const cce_opts* opts);
+
+/*
+ * Forward for callers that cannot allocate device memory and have no workspace to lend: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, kernels and results as cce_forward_ex (bit-identical), except that
+ * opts->workspace / workspace_bytes are ignored: the scratch (the per-split (max, sum) pairs)
+ * lives in a static device array inside the library, cce_noalloc_scratch_bytes() = 8 MiB per
+ * GPU the library runs on, held until the process ends.  The call allocates and frees
+ * nothing, on the device or through any library.  A problem whose forward workspace
+ * (cce_workspace_bytes(CCE_OP_FORWARD, ...)) exceeds the array is refused with CCE_ESCRATCH
+ * before anything is launched: at 8 splits that is N > 131072 tokens, and any call with
+ * CCE_COMPACT_IGNORED whose copy of E does not fit.
+ * Every call on one GPU shares that GPU's array, which keeps the previous call's contents
+ * (never read: each call writes all the partials it merges).  Calls that overlap on one GPU
+ * (different streams, different threads) race on it; calls on one stream are safe.
+ */
+int cce_forward_noalloc(const void* E, const void* C, const int64_t* targets,
+                        int64_t N, int64_t D, int64_t V,
+                        float softcap, int64_t ignore_index,
+                        float* out_loss, float* out_lse, const cce_opts* opts);
+
+/* Size in bytes of the static scratch array behind cce_forward_noalloc. */
+size_t cce_noalloc_scratch_bytes(void);
 
 /*
  * Backward (Alg. 4, the merged linear-cross-entropy backward; gradient formula

@@ -62,6 +62,10 @@ def load() -> ctypes.CDLL:
     bwd = [vp, vp, vp, i64, i64, i64, f32, i64, vp, vp, vp, vp]
     lib.cce_forward.argtypes = fwd
     lib.cce_forward_ex.argtypes = fwd + [po]
+    lib.cce_forward_noalloc.argtypes = fwd + [po]
+    lib.cce_forward_noalloc.restype = ctypes.c_int
+    lib.cce_noalloc_scratch_bytes.argtypes = []
+    lib.cce_noalloc_scratch_bytes.restype = sz
     lib.cce_backward.argtypes = bwd
     lib.cce_backward_ex.argtypes = bwd + [po]
     for f in (lib.cce_forward, lib.cce_forward_ex, lib.cce_backward, lib.cce_backward_ex):
@@ -163,6 +167,19 @@ def cce_forward_ex(E, C, targets, softcap: float, ignore_index: int, opts: CceOp
     _check(load().cce_forward_ex(E.data_ptr(), C.data_ptr(), targets.data_ptr(), N, D, V, float(softcap),
                                  int(ignore_index), out_loss.data_ptr(), out_lse.data_ptr(), ctypes.byref(opts)))
     return out_loss, out_lse
+
+
+def cce_forward_noalloc(E, C, targets, softcap: float, ignore_index: int, opts: CceOpts, out_loss, out_lse):
+    """Forward on the library's static scratch.  The outputs are required arguments: this wrapper
+    allocates nothing either."""
+    N, D, V = _shapes(E, C, targets)
+    _check(load().cce_forward_noalloc(E.data_ptr(), C.data_ptr(), targets.data_ptr(), N, D, V, float(softcap),
+                                      int(ignore_index), out_loss.data_ptr(), out_lse.data_ptr(), ctypes.byref(opts)))
+    return out_loss, out_lse
+
+
+def cce_noalloc_scratch_bytes() -> int:
+    return int(load().cce_noalloc_scratch_bytes())
 
 
 def _bwd_args(E, C, targets, lse, dloss, out_dE, out_dC):

@@ -16,6 +16,7 @@ namespace {
 using namespace cce;
 
 thread_local char g_hip_error[256] = "no HIP error recorded";
+thread_local char g_noalloc_error[256] = "problem too large for the static scratch of cce_forward_noalloc";
 
 int hip_fail(hipError_t e, const char* what) {
   snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s", what, hipGetErrorString(e));
@@ -114,6 +115,31 @@ int helpers_for_device(Helpers** out) {
     h.ready = true;
   }
   *out = &h;
+  return CCE_OK;
+}
+
+// Scratch of cce_forward_noalloc: device memory that exists as long as the library is loaded, so
+// that the call needs no allocation at all.  The name below is a host-side stand-in, not a
+// device address: host code uses the address hipGetSymbolAddress returns for the current device
+// (every GPU holds its own copy), looked up once per device and kept.
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+void* g_scratch_ptr[kMaxDevices];   // per device, nullptr = not looked up yet
+std::mutex g_scratch_mutex;
+
+int static_scratch(void** out) {
+  int dev = 0;
+  CCE_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return CCE_EUNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    CCE_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));   // address on the current device
+    if (!ptr) return hip_fail(hipErrorInvalidSymbol, "hipGetSymbolAddress(scratch)");
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
   return CCE_OK;
 }
 
@@ -359,6 +385,7 @@ const char* cce_strerror(int status) {
     case CCE_EWORKSPACE: return "workspace missing or too small (see cce_workspace_bytes)";
     case CCE_EUNSUPPORTED: return "unsupported dtype, flag combination, or a size beyond the kernels' 32-bit offsets";
     case CCE_EHIP: return g_hip_error;
+    case CCE_ESCRATCH: return g_noalloc_error;
     default: return "unknown status";
   }
 }
@@ -647,6 +674,30 @@ int cce_forward(const void* E, const void* C, const int64_t* targets, int64_t N,
   if (st != CCE_OK) return st;
   return cce_forward_ex(E, C, targets, N, D, V, softcap, ignore_index, out_loss, out_lse, &o);
 }
+
+int cce_forward_noalloc(const void* E, const void* C, const int64_t* targets, int64_t N, int64_t D, int64_t V,
+                        float softcap, int64_t ignore_index, float* out_loss, float* out_lse, const cce_opts* opts) {
+  // every check of cce_forward_ex that does not concern the workspace, before anything else
+  int st = check_common(E, C, targets, N, D, V, softcap, opts);
+  if (st != CCE_OK) return st;
+  if (!out_loss || !out_lse) return CCE_EINVAL;
+  const size_t need = plan_forward(N, D, V, opts).total_bytes;
+  if (need > kStaticScratchBytes) {
+    snprintf(g_noalloc_error, sizeof(g_noalloc_error),
+             "cce_forward_noalloc: this call needs %zu bytes of scratch, the library's static array holds %zu "
+             "(use cce_forward_ex with a caller workspace)", need, kStaticScratchBytes);
+    return CCE_ESCRATCH;
+  }
+  cce_opts o = *opts;
+  st = static_scratch(&o.workspace);
+  if (st != CCE_OK) return st;
+  o.workspace_bytes = kStaticScratchBytes;
+  // The forward kernels write every (split, token) partial the finalize kernel reads, so nothing of
+  // the array has to start at zero: what an earlier call left in it is never read.
+  return cce_forward_ex(E, C, targets, N, D, V, softcap, ignore_index, out_loss, out_lse, &o);
+}
+
+size_t cce_noalloc_scratch_bytes(void) { return kStaticScratchBytes; }
 
 int cce_backward(const void* E, const void* C, const int64_t* targets, int64_t N, int64_t D, int64_t V,
                  float softcap, int64_t ignore_index, const float* lse, const float* dLoss, void* out_dE,
