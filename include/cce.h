@@ -11,13 +11,15 @@
  *     caller owns every buffer; the library only reads inputs and writes the
  *     outputs / the workspace named in the call.
  *   - E is [N, D] and C is [V, D], row-major, contiguous (leading dimension D):
- *     the paper's D x N / D x |V| matrices "indexed by column" (Appendix A).
+ *     the paper's D x N / D x |V| matrices, whose columns are the tokens / the
+ *     vocabulary entries (Appendix A), stored with that index outermost.
  *     Element type: bfloat16 (CCE_BF16) or float (CCE_F32); E, C, out_dE and
  *     out_dC share it.  Pointers must be 16-byte aligned.
  *   - targets is int64 [N].  A token is "ignored" when its target equals
  *     ignore_index or lies outside [0, V): it gets loss 0, contributes nothing
  *     to dE / dC, and its dLoss entry is not read (Appendix B: ignored tokens
- *     change neither loss nor gradient).
+ *     change neither loss nor gradient).  Targets outside [0, V) other than
+ *     ignore_index are counted (cce_forward_target_stats).
  *   - softcap == 0 disables logit soft-capping; softcap > 0 replaces every
  *     logit z by softcap * tanh(z / softcap) (the soft-capping named in
  *     Table A2; formula is this library's reading).  Negative or NaN: CCE_EINVAL.
@@ -25,9 +27,15 @@
  *     for the plain entry points) and never synchronise it.  Work that the
  *     library spreads over helper streams is joined back into that stream
  *     before the call returns.
+ *   - The library never allocates, frees or synchronises device memory: all
+ *     scratch is the caller's (opts->workspace, or the buffer lent with
+ *     cce_set_workspace for the plain entry points).  Per device it creates
+ *     three helper streams and a few events on the first backward call.
  *   - Return value: CCE_OK (0) or a negative cce_status.  On CCE_EINVAL,
- *     CCE_EUNSUPPORTED and CCE_EWORKSPACE nothing has been launched and no
- *     output has been written.
+ *     CCE_EUNSUPPORTED, CCE_EWORKSPACE and CCE_ESCRATCH nothing has been
+ *     launched and no output has been written.  After CCE_EHIP (a launch or
+ *     runtime call failed part-way) the outputs are undefined; helper streams
+ *     that had been given work are still joined back into the caller's stream.
  *   - Results are bitwise reproducible from call to call: no atomics and no
  *     lock-ordered reductions are used (the paper's Alg. 2 / Alg. 4 use
  *     spin-locks; Section 4.2 itself notes alternatives may be preferable).
@@ -59,7 +67,11 @@ enum { CCE_BF16 = 0, CCE_F32 = 1 };
 enum {
   CCE_FILTER_DE = 1u << 0,   /* apply gradient filtering to dE (Section 4.3) */
   CCE_FILTER_DC = 1u << 1,   /* apply gradient filtering to dC; clearing only this bit is the
-                                paper's "CCE-Kahan-FullC" choice, clearing only FILTER_DE "FullE" */
+                                paper's "CCE-Kahan-FullC" choice, clearing only FILTER_DE "FullE".
+                                MFMA path with N > 131072 tokens: dC is computed unfiltered whatever this
+                                bit says (a filtered contraction over tokens keeps its list of kept
+                                64-token steps in LDS, 2048 entries); still within every tolerance, since
+                                the filter only ever drops terms */
   CCE_VOCAB_SORT = 1u << 2,  /* backward only: walk the vocabulary in descending order of each entry's
                                 mean logit over the batch (Section 4.3, "Vocabulary sorting"), so that
                                 entries with non-negligible softmax mass share filter blocks.  The mean
@@ -133,9 +145,9 @@ void cce_default_opts(int dtype, cce_opts* opts);
  * registers / LDS.  (CCE_COMPACT_IGNORED adds a copy of E, CCE_SKIP_TILES the
  * caller's block_max record.)
  *
- * cce_forward: bf16 inputs, null stream, library-owned workspace (allocated
- * with hipMalloc on first use per device, grown when a larger problem arrives,
- * kept until the process ends; calls on one device must not overlap).
+ * cce_forward: bf16 inputs, default options, null stream, scratch taken from the
+ * buffer lent with cce_set_workspace (CCE_EWORKSPACE when none is registered on
+ * the current device or it is smaller than cce_workspace_bytes(CCE_OP_FORWARD)).
  */
 int cce_forward(const void* E, const void* C, const int64_t* targets,
                 int64_t N, int64_t D, int64_t V,
@@ -156,8 +168,8 @@ int cce_forward_ex(const void* E, const void* C, const int64_t* targets,
  * GPU the library runs on, held until the process ends.  The call allocates and frees
  * nothing, on the device or through any library.  A problem whose forward workspace
  * (cce_workspace_bytes(CCE_OP_FORWARD, ...)) exceeds the array is refused with CCE_ESCRATCH
- * before anything is launched: at 8 splits that is N > 131072 tokens, and any call with
- * CCE_COMPACT_IGNORED whose copy of E does not fit.
+ * before anything is launched: at the 8 vocabulary splits of a large batch that is N >= 131072
+ * tokens, and any call with CCE_COMPACT_IGNORED whose copy of E does not fit.
  * Every call on one GPU shares that GPU's array, which keeps the previous call's contents
  * (never read: each call writes all the partials it merges).  Calls that overlap on one GPU
  * (different streams, different threads) race on it; calls on one stream are safe.
@@ -191,7 +203,9 @@ size_t cce_noalloc_scratch_bytes(void);
  * Work that the call spreads over the library's helper streams is joined back into
  * opts->stream before it returns; the whole call can be captured into a HIP graph.
  *
- * cce_backward: bf16, null stream, filtering on at 2^-12, library-owned workspace.
+ * cce_backward: bf16, null stream, filtering on at 2^-12, scratch taken from the buffer
+ * lent with cce_set_workspace (any size from CCE_OP_BACKWARD_MIN up; CCE_EWORKSPACE
+ * when none is registered on the current device or it is smaller than that).
  */
 int cce_backward(const void* E, const void* C, const int64_t* targets,
                  int64_t N, int64_t D, int64_t V,
@@ -205,6 +219,18 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets,
                     const float* lse, const float* dLoss,
                     void* out_dE, void* out_dC, const cce_opts* opts);
 
+/*
+ * Lends the plain entry points (cce_forward, cce_backward) their scratch on the CURRENT device:
+ * `workspace` is device memory of `workspace_bytes` bytes, 256-byte aligned, owned by the caller,
+ * who keeps it alive and unused by anything else until it registers another buffer or NULL / 0
+ * (which withdraws it).  Forward and backward calls share it, so calls that use it must not
+ * overlap (one stream, or ordered by the caller).  cce_workspace_bytes(CCE_OP_BACKWARD, ...) of the
+ * largest problem covers both.  The spec signatures carry no workspace argument and the
+ * library does not allocate: this call is how memory reaches them.  Host-side only (nothing is
+ * launched).  Returns CCE_OK, CCE_EINVAL (misaligned, or pointer / size inconsistent) or CCE_EHIP.
+ */
+int cce_set_workspace(void* workspace, size_t workspace_bytes);
+
 /* Workspace size in bytes for `op` (CCE_OP_*) at this shape and these options
  * (dtype and flags are read; workspace fields are not).  0 on invalid arguments. */
 size_t cce_workspace_bytes(int op, int64_t N, int64_t D, int64_t V, const cce_opts* opts);
@@ -217,8 +243,17 @@ size_t cce_block_max_bytes(int64_t N, int64_t V);
 void cce_filter_block(int64_t N, int64_t D, int64_t V, const cce_opts* opts,
                       int* block_rows, int* block_cols);
 
+/* Number of targets of the last forward call that used this workspace (NULL: the buffer lent
+ * with cce_set_workspace) which were neither ignore_index nor inside [0, V).  Such targets are
+ * treated as ignored (no access out of bounds, loss 0, no gradient); this call is how a caller
+ * learns of them: the paper is silent on invalid labels, and a device-side count read after the
+ * fact keeps the hot path free of synchronisation.  Synchronises `stream` (a reporting call).
+ * Not available for cce_forward_noalloc, whose scratch is not addressable by the caller. */
+int cce_forward_target_stats(const void* workspace, void* stream, uint64_t* out_of_range);
+
 /* Host-side counters of the last cce_backward(_ex) call that used this
- * workspace: number of filter blocks visited and number kept.  Synchronises
+ * workspace (NULL: the buffer lent with cce_set_workspace): number of filter blocks
+ * visited and number kept.  Synchronises
  * `stream` (this is a reporting call, not part of the hot path).
  * Returns CCE_OK or a negative status. */
 int cce_backward_filter_stats(const void* workspace, void* stream,

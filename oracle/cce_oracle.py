@@ -13,7 +13,7 @@ Definitions followed (paper section / equation):
     The returned `loss` is the negative log-likelihood  -l_i  (so that C = 0
     gives log|V|), and is 0 for ignored tokens.
   * Section 4.2, Alg. 2: LSE_i = log sum_j exp(a_ij), evaluated with the row
-    maximum subtracted (the "numerically stable implementation with max").
+    maximum subtracted so that no exponential overflows.
   * Section 4.3 (gradient of the LSE term) and Alg. 4 (merged backward):
         S = exp(A - LSE),  G = S - onehot(x)   (sign follows the NLL),
         dE = (G . dloss) C,   dC = (G . dloss)^T E.
@@ -23,8 +23,9 @@ Definitions followed (paper section / equation):
     used here: a = cap * tanh(z / cap), applied to every logit including the
     target's, with derivative 1 - (a/cap)^2 chained into the gradient.
 
-Layout: E is [N, D], C is [V, D] (the paper's D x N and D x |V| matrices
-"indexed by column", stored row-major), targets int64 [N].
+Layout: E is [N, D], C is [V, D] (the paper's D x N and D x |V| matrices of
+Appendix A, whose columns are the tokens / vocabulary entries, stored with that
+index outermost), targets int64 [N].
 
 Every function is pinned by tests/test_oracle_pins.py against closed forms,
 finite differences, scipy/torch library routines and brute force; none is

@@ -11,7 +11,6 @@ from .binding import (  # noqa: F401
     CCE_OP_FORWARD, CCE_OP_BACKWARD, CCE_OP_BACKWARD_MIN, CCE_OP_BACKWARD_WIDE,
     CceError, CceOpts, LIB_PATH,
     load, cce_default_opts, cce_workspace_bytes, cce_block_max_bytes, cce_filter_block, cce_strerror,
-    cce_forward, cce_forward_ex, cce_forward_noalloc, cce_noalloc_scratch_bytes, cce_backward, cce_backward_ex, cce_backward_filter_stats,
-    make_opts, cce_probe_mfma, cce_probe_copy,
+    cce_forward, cce_forward_ex, cce_forward_noalloc, cce_noalloc_scratch_bytes, cce_backward, cce_backward_ex, cce_backward_filter_stats, cce_forward_target_stats,
+    make_opts, cce_set_workspace,
 )
-from .autograd import linear_cross_entropy  # noqa: F401

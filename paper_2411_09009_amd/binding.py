@@ -72,10 +72,10 @@ def load() -> ctypes.CDLL:
         f.restype = ctypes.c_int
     lib.cce_backward_filter_stats.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint64)]
     lib.cce_backward_filter_stats.restype = ctypes.c_int
-    lib.cce_probe_mfma.argtypes = [vp, vp, ctypes.c_int, ctypes.c_int, vp]
-    lib.cce_probe_mfma.restype = ctypes.c_int
-    lib.cce_probe_copy.argtypes = [vp, vp, sz, vp]
-    lib.cce_probe_copy.restype = ctypes.c_int
+    lib.cce_forward_target_stats.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_uint64)]
+    lib.cce_forward_target_stats.restype = ctypes.c_int
+    lib.cce_set_workspace.argtypes = [vp, sz]
+    lib.cce_set_workspace.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -122,6 +122,20 @@ def make_opts(dtype: int, flags: Optional[int] = None, filter_eps: Optional[floa
     return o
 
 
+_lent = {}   # device index -> the tensor lent to the plain entry points (kept alive here)
+
+
+def cce_set_workspace(workspace: Optional[torch.Tensor]) -> None:
+    """Lends `workspace` (a device tensor; None withdraws it) to cce_forward / cce_backward on its device."""
+    if workspace is None:
+        _check(load().cce_set_workspace(None, 0))
+        _lent.pop(torch.cuda.current_device(), None)
+        return
+    with torch.cuda.device(workspace.device):
+        _check(load().cce_set_workspace(workspace.data_ptr(), workspace.numel() * workspace.element_size()))
+        _lent[workspace.device.index] = workspace
+
+
 def cce_workspace_bytes(op: int, N: int, D: int, V: int, opts: CceOpts) -> int:
     return int(load().cce_workspace_bytes(int(op), int(N), int(D), int(V), ctypes.byref(opts)))
 
@@ -149,7 +163,7 @@ def _shapes(E: torch.Tensor, C: torch.Tensor, targets: torch.Tensor):
 
 
 def cce_forward(E, C, targets, softcap: float = 0.0, ignore_index: int = -100, out_loss=None, out_lse=None):
-    """Plain entry point: bf16, null stream, library-owned workspace."""
+    """Plain entry point: bf16, null stream, scratch from the buffer lent with cce_set_workspace."""
     N, D, V = _shapes(E, C, targets)
     if E.dtype != torch.bfloat16:
         raise TypeError("cce_forward takes bfloat16; use cce_forward_ex for float32")
@@ -193,7 +207,7 @@ def _bwd_args(E, C, targets, lse, dloss, out_dE, out_dC):
 
 
 def cce_backward(E, C, targets, lse, dloss, softcap: float = 0.0, ignore_index: int = -100, out_dE=None, out_dC=None):
-    """Plain entry point: bf16, null stream, filtering on at 2^-12, library-owned workspace."""
+    """Plain entry point: bf16, null stream, filtering on at 2^-12, scratch from the lent buffer."""
     N, D, V, out_dE, out_dC = _bwd_args(E, C, targets, lse, dloss, out_dE, out_dC)
     if E.dtype != torch.bfloat16:
         raise TypeError("cce_backward takes bfloat16; use cce_backward_ex for float32")
@@ -220,23 +234,9 @@ def cce_backward_filter_stats(workspace: Optional[torch.Tensor] = None, stream: 
     return total.value, kept.value
 
 
-def _hip_check(code: int, what: str) -> None:
-    if code != 0:
-        raise RuntimeError("%s failed with hipError_t %d" % (what, code))
-
-
-def cce_probe_mfma(frags: torch.Tensor, out: torch.Tensor, blocks: int, iters: int, stream: Optional[int] = None) -> None:
-    """Measurement helper (include/cce_probe.h): register-resident MFMA loop."""
-    if frags.numel() * frags.element_size() < 384 * 16 or out.numel() < blocks * 512 or out.dtype != torch.float32:
-        raise ValueError("frags needs 384 * 16 bytes, out blocks * 512 floats")
+def cce_forward_target_stats(workspace: Optional[torch.Tensor] = None, stream: Optional[int] = None) -> int:
+    n = ctypes.c_uint64(0)
+    ws = None if workspace is None else workspace.data_ptr()
     st = torch.cuda.current_stream().cuda_stream if stream is None else int(stream)
-    _hip_check(load().cce_probe_mfma(frags.data_ptr(), out.data_ptr(), int(blocks), int(iters), st), "cce_probe_mfma")
-
-
-def cce_probe_copy(dst: torch.Tensor, src: torch.Tensor, stream: Optional[int] = None) -> None:
-    """Measurement helper (include/cce_probe.h): plain copy of src into dst."""
-    nbytes = src.numel() * src.element_size()
-    if dst.numel() * dst.element_size() != nbytes or nbytes % 16:
-        raise ValueError("dst and src must have the same size, a multiple of 16 bytes")
-    st = torch.cuda.current_stream().cuda_stream if stream is None else int(stream)
-    _hip_check(load().cce_probe_copy(dst.data_ptr(), src.data_ptr(), nbytes, st), "cce_probe_copy")
+    _check(load().cce_forward_target_stats(ws, st, ctypes.byref(n)))
+    return n.value

@@ -16,7 +16,10 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_DIR = os.path.join(HERE, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libcce.so")
-SOURCES = ["cce_api.hip", "plain_kernels.hip", "fwd_mfma.hip", "bwd_mfma.hip", "sort_kernels.hip", "mfma_probe.hip"]
+SOURCES = ["cce_api.hip", "plain_kernels.hip", "fwd_mfma.hip", "bwd_mfma.hip", "sort_kernels.hip"]
+# the benchmark's measurement probes: a shared object of their own, loaded by bench.py only
+PROBE_LIB_PATH = os.path.join(LIB_DIR, "libcce_probe.so")
+PROBE_SOURCES = [os.path.join("probe", "probe_kernels.hip")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -37,19 +40,22 @@ def _run(cmd):
 
 
 def build(verbose: bool = False) -> str:
+    """Compiles libcce.so (the product) and libcce_probe.so (bench.py's probes); returns the former's path."""
     os.makedirs(LIB_DIR, exist_ok=True)
     with tempfile.TemporaryDirectory(prefix="cce_build_") as tmp:
-        objs = [os.path.join(tmp, s.replace(".hip", ".o")) for s in SOURCES]
-        cmds = [[HIPCC, *FLAGS, "-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)]
+        every = SOURCES + PROBE_SOURCES
+        objs = [os.path.join(tmp, os.path.basename(s).replace(".hip", ".o")) for s in every]
+        cmds = [[HIPCC, *FLAGS, "-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(every, objs)]
         with ThreadPoolExecutor(max_workers=min(6, len(cmds))) as ex:
             for out in ex.map(_run, cmds):
                 if verbose and out.strip():
                     print(out)
-        tmp_lib = os.path.join(tmp, "libcce.so")
-        _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", tmp_lib])
-        staged = LIB_PATH + ".tmp"
-        shutil.copyfile(tmp_lib, staged)
-        os.replace(staged, LIB_PATH)
+        for path, group in ((LIB_PATH, objs[:len(SOURCES)]), (PROBE_LIB_PATH, objs[len(SOURCES):])):
+            tmp_lib = os.path.join(tmp, os.path.basename(path))
+            _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *group, "-o", tmp_lib])
+            staged = path + ".tmp"
+            shutil.copyfile(tmp_lib, staged)
+            os.replace(staged, path)
     return LIB_PATH
 
 

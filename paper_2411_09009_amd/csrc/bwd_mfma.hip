@@ -522,13 +522,13 @@ hipError_t launch_tile_lists(const TileListParams& p, hipStream_t stream) {
   return hipGetLastError();
 }
 
-hipError_t launch_bwd_recompute_mfma(const BwdCommon& c, const BwdMfmaSlab& s, hipStream_t stream) {
+hipError_t launch_bwd_recompute_mfma(const BwdCommon& c, const BwdMfmaSlab& s, int cus, hipStream_t stream) {
   const int n_tiles = s.Np / kTileC, v_tiles = s.vs / kTileR;
-  const int want = 256;
+  const int want = cus > 0 ? cus : 256;
   const SplitPlan plan = make_split_plan(c.N, v_tiles, want, 1 << 30);
   if (s.tile_list) {
     // one share of the work list per CU, at most one per tile
-    int groups = 256;
+    int groups = (want + kXcds - 1) / kXcds * kXcds;
     if (groups > n_tiles * v_tiles) groups = (n_tiles * v_tiles + kXcds - 1) / kXcds * kXcds;
     dim3 grid(groups);
     if (c.softcap > 0.f)

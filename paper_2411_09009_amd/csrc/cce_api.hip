@@ -51,33 +51,23 @@ int cu_count() {
   return n;
 }
 
-// Library-owned workspace for the plain entry points: one buffer per device,
-// grown on demand, kept until the process ends.
-struct OwnedWorkspace {
+// Workspace lent to the plain entry points (cce_set_workspace): one registration per device.
+// The library never allocates, frees or synchronises; without a registration the plain calls
+// return CCE_EWORKSPACE.
+struct LentWorkspace {
   void* ptr = nullptr;
   size_t bytes = 0;
 };
-OwnedWorkspace g_owned[kMaxDevices];
-std::mutex g_owned_mutex;
+LentWorkspace g_lent[kMaxDevices];
+std::mutex g_lent_mutex;
 
-int owned_workspace(size_t need, void** out) {
+int lent_workspace(LentWorkspace* out) {
   int dev = 0;
   CCE_HIP(hipGetDevice(&dev));
   if (dev < 0 || dev >= kMaxDevices) return CCE_EUNSUPPORTED;
-  std::lock_guard<std::mutex> lock(g_owned_mutex);
-  OwnedWorkspace& w = g_owned[dev];
-  if (w.bytes < need) {
-    if (w.ptr) {
-      CCE_HIP(hipDeviceSynchronize());   // earlier calls may still be using the old buffer
-      CCE_HIP(hipFree(w.ptr));
-      w.ptr = nullptr;
-      w.bytes = 0;
-    }
-    CCE_HIP(hipMalloc(&w.ptr, need));
-    w.bytes = need;
-  }
-  *out = w.ptr;
-  return CCE_OK;
+  std::lock_guard<std::mutex> lock(g_lent_mutex);
+  *out = g_lent[dev];
+  return out->ptr ? CCE_OK : CCE_EWORKSPACE;
 }
 
 // Helper streams of the MFMA backward pass: the two gradient products of a vocabulary
@@ -95,6 +85,7 @@ struct Helpers {
   hipEvent_t recomputed[kEventRing] = {};
   hipEvent_t dC_done[kEventRing] = {};
   hipEvent_t dE_done[kEventRing] = {};
+  hipEvent_t joined[3] = {};          // one per product stream: everything enqueued on it so far
 };
 Helpers g_helpers[kMaxDevices];
 
@@ -112,6 +103,7 @@ int helpers_for_device(Helpers** out) {
       CCE_HIP(hipEventCreateWithFlags(&h.dC_done[i], hipEventDisableTiming));
       CCE_HIP(hipEventCreateWithFlags(&h.dE_done[i], hipEventDisableTiming));
     }
+    for (auto& ev : h.joined) CCE_HIP(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
     h.ready = true;
   }
   *out = &h;
@@ -181,7 +173,7 @@ struct FwdPlan {
   SplitPlan plan;                // MFMA path, for N tokens
   int want_wgs, round_cap;
   unsigned grid;
-  size_t partial_bytes;
+  size_t off_partial, partial_bytes;
   // ignored tokens removed (CCE_COMPACT_IGNORED, MFMA path): index list, count, compacted copy of E
   bool compact;
   size_t off_idx, off_count, off_Ec;
@@ -212,6 +204,7 @@ FwdPlan plan_forward(int64_t N, int64_t D, int64_t V, const cce_opts* o) {
     p.tiles_per_split = (p.v_tiles + splits - 1) / splits;
     p.splits = (p.v_tiles + p.tiles_per_split - 1) / p.tiles_per_split;
   }
+  p.off_partial = 256;   // the workspace starts with the forward's counters (ForwardStats)
   size_t rows = (size_t)p.splits * (size_t)N;
   if (p.compact) {
     // the device-side plan for fewer tokens uses more splits of fewer rows
@@ -219,7 +212,7 @@ FwdPlan plan_forward(int64_t N, int64_t D, int64_t V, const cce_opts* o) {
     if (most > rows) rows = most;
   }
   p.partial_bytes = align_up(rows * sizeof(LsePartial), 256);
-  p.total_bytes = p.partial_bytes;
+  p.total_bytes = p.off_partial + p.partial_bytes;
   if (p.compact) {
     p.off_idx = p.total_bytes;   p.total_bytes += align_up((size_t)N * 4, 256);
     p.off_count = p.total_bytes; p.total_bytes += 256;
@@ -431,7 +424,8 @@ int cce_forward_ex(const void* E, const void* C, const int64_t* targets, int64_t
   const FwdPlan plan = plan_forward(N, D, V, opts);
   if (!opts->workspace || opts->workspace_bytes < plan.total_bytes) return CCE_EWORKSPACE;
   hipStream_t stream = (hipStream_t)opts->stream;
-  LsePartial* partial = (LsePartial*)opts->workspace;
+  ForwardStats* fstats = (ForwardStats*)opts->workspace;
+  LsePartial* partial = (LsePartial*)((char*)opts->workspace + plan.off_partial);
   const int* n_dev = nullptr;
   const int* idx = nullptr;
   if (plan.compact) {
@@ -440,7 +434,7 @@ int cce_forward_ex(const void* E, const void* C, const int64_t* targets, int64_t
     int* idx_w = (int*)(ws + plan.off_idx);
     int* count_w = (int*)(ws + plan.off_count);
     bf16* Ec = (bf16*)(ws + plan.off_Ec);
-    CCE_HIP(launch_compact_tokens(targets, (int)N, (int)V, ignore_index, idx_w, count_w, stream));
+    CCE_HIP(launch_compact_tokens(targets, (int)N, (int)V, ignore_index, idx_w, count_w, &fstats->bad_targets, stream));
     CCE_HIP(launch_gather_tokens((const bf16*)E, idx_w, count_w, (int)N, (int)D, Ec, stream));
     // ignored tokens: loss 0 (and lse 0, documented as unspecified)
     CCE_HIP(launch_fill_f32(out_loss, N, 0.f, stream));
@@ -462,6 +456,7 @@ int cce_forward_ex(const void* E, const void* C, const int64_t* targets, int64_t
     p.plan = plan.plan;
     p.want_wgs = plan.want_wgs; p.round_cap = plan.round_cap;
     p.grid = plan.grid;
+    p.bad_targets = plan.compact ? nullptr : &fstats->bad_targets;
     if ((opts->flags & CCE_SKIP_TILES) && opts->block_max) {
       p.block_max = (uint16_t*)opts->block_max;
       p.block_max_stride = (int)round_up(N, 256);
@@ -474,6 +469,7 @@ int cce_forward_ex(const void* E, const void* C, const int64_t* targets, int64_t
     p.softcap = softcap;
     p.partial = partial;
     p.splits = plan.splits; p.tiles_per_split = plan.tiles_per_split;
+    p.bad_targets = &fstats->bad_targets;
     CCE_HIP(launch_fwd_lse_plain(p, stream));
   }
   FinalizeParams f{};
@@ -483,10 +479,149 @@ int cce_forward_ex(const void* E, const void* C, const int64_t* targets, int64_t
   f.partial = partial; f.splits = plan.splits;
   f.out_loss = out_loss; f.out_lse = out_lse;
   f.n_dev = n_dev; f.idx = idx;
+  f.bad_targets = plan.compact ? nullptr : &fstats->bad_targets;
   f.v_tiles = plan.v_tiles; f.want_wgs = plan.want_wgs; f.round_cap = plan.round_cap;
   CCE_HIP(launch_finalize(f, stream));
   return CCE_OK;
 }
+
+}  // extern "C"
+
+namespace {
+
+// Everything the MFMA backward enqueues, slab after slab.  `forked[i]` is set as soon as work has
+// been put on helper stream i, so that the caller can join exactly those streams back into the
+// caller's stream whether this returns success or a failure half way.
+int enqueue_backward_mfma(const BwdCommon& c0, const BwdPlan& plan, Helpers* h, const void* C, const int64_t* targets,
+                          const float* lse, int64_t N, int64_t D, int64_t V, int64_t vs, bool sort, bool lists_layout,
+                          bool compact, const void* E, void* out_dC, const cce_opts* opts, char* ws,
+                          hipStream_t stream, bool (&forked)[3], int* ksplit_out, const int** n_dev_out,
+                          const int** idx_out) {
+  BwdCommon c = c0;
+  const int64_t ignore_index = c.ignore_index;
+  BwdMfmaSlab s{};
+  s.Np = (int)plan.Np;
+  s.dEacc = (float*)(ws + plan.off_dEacc);
+  s.ksplit = dE_ksplit(N, D);
+  s.dE_part_stride = N * D;
+  *ksplit_out = s.ksplit;
+  const bool serial = (opts->flags & CCE_SINGLE_STREAM) != 0;
+  // a filtered contraction keeps its list of 64-wide steps in LDS; longer ones (N > 131072) run unfiltered
+  if (plan.Np / 64 > kMaxFilteredKSteps) c.filter_dC = 0;
+  CCE_HIP(launch_clear_stats(c.stats, stream));
+  // helper work may not start before the caller's earlier work on `stream` (which may produce C)
+  if (!serial) CCE_HIP(hipEventRecord(h->started, stream));
+  if (compact) {
+    int* idx_w = (int*)(ws + plan.off_idx);
+    int* count_w = (int*)(ws + plan.off_count);
+    bf16* Ec = (bf16*)(ws + plan.off_Ec);
+    CCE_HIP(launch_compact_tokens(targets, (int)N, (int)V, ignore_index, idx_w, count_w, nullptr, stream));
+    CCE_HIP(launch_gather_tokens((const bf16*)E, idx_w, count_w, (int)N, (int)D, Ec, stream));
+    c.E = Ec;              // the vocabulary sort below keeps using the caller's E (its key is a batch mean)
+    c.n_dev = count_w;
+    c.idx = idx_w;
+    *n_dev_out = count_w;
+    *idx_out = idx_w;
+  }
+  if (sort) {
+    VocabSortParams v{};
+    v.E = (const bf16*)E; v.C = (const bf16*)C; v.targets = targets;
+    v.N = (int)N; v.D = (int)D; v.V = (int)V; v.ignore_index = ignore_index;
+    v.partial = (float*)(ws + plan.off_partial);
+    v.mean = (float*)(ws + plan.off_mean);
+    v.key = (float*)(ws + plan.off_key);
+    v.key_sorted = (float*)(ws + plan.off_key_sorted);
+    v.index = (int*)(ws + plan.off_index);
+    v.perm = (int*)(ws + plan.off_perm);
+    v.inverse = (int*)(ws + plan.off_inverse);
+    v.targets_sorted = (int64_t*)(ws + plan.off_targets);
+    v.temp = ws + plan.off_sort_temp;
+    v.temp_bytes = plan.sort_temp_bytes;
+    CCE_HIP(launch_vocab_sort(v, stream));   // the scratch size was checked before the first launch
+    c.targets = v.targets_sorted;    // from here on the vocabulary is indexed by sorted position
+    s.perm = v.perm;
+  }
+  const bool use_lists = lists_layout && opts->block_max && c.filter_dE && c.filter_dC && c.eps > 0.f;
+  const int64_t slab_tiles = vs / 256;
+  if (use_lists) {
+    TileListParams t{};
+    t.block_max = (const uint16_t*)opts->block_max;
+    t.stride = (int)plan.Np;
+    t.targets = targets; t.lse = lse;
+    t.n_dev = c.n_dev; t.idx = c.idx;
+    t.N = (int)N; t.V = (int)V; t.ignore_index = ignore_index;
+    t.log_eps = logf(c.eps) - 0.02f;   // margin for the fp32 rounding of lse and of the recorded maxima
+    t.n_tiles = (int)(plan.Np / 256); t.v_tiles = (int)((V + 255) / 256);
+    t.slab_tiles = (int)slab_tiles;
+    t.slabs = (int)((t.v_tiles + slab_tiles - 1) / slab_tiles);
+    t.tile_flag = (uint8_t*)(ws + plan.off_tile_flag);
+    t.tile_list = (uint32_t*)(ws + plan.off_tile_list);
+    t.tile_count = (uint32_t*)(ws + plan.off_tile_count);
+    CCE_HIP(launch_tile_lists(t, stream));
+  }
+  const int64_t n_slabs = (round_up(V, 256) + vs - 1) / vs;
+  uint32_t* flags_all = (uint32_t*)(ws + plan.off_flags[0]);
+  CCE_HIP(launch_zero_flags(flags_all, n_slabs * (int64_t)plan.flag_region_words, stream));
+  const int cus = cu_count();
+  int64_t slab = 0;
+  for (int64_t v0 = 0; v0 < V; v0 += vs, ++slab) {
+    const int b = (int)(slab % kSlabBuffers), e = (int)(slab % kEventRing);
+    const int64_t vs_this = (round_up(V - v0, 256) < vs) ? round_up(V - v0, 256) : vs;
+    s.v0 = (int)v0;
+    s.vs = (int)vs_this;
+    s.first = v0 == 0;
+    s.GZ = (bf16*)(ws + plan.off_GZ[b]);
+    s.flags_nv = flags_all + slab * (int64_t)plan.flag_region_words;
+    s.flags_vn = s.flags_nv + (plan.Np / 256) * (vs_this / 64);
+    if (!serial && slab >= kSlabBuffers) {
+      // this slab's buffers were last read by the products of slab - kSlabBuffers
+      const int e2 = (int)((slab - kSlabBuffers) % kEventRing);
+      CCE_HIP(hipStreamWaitEvent(stream, h->dC_done[e2], 0));
+      CCE_HIP(hipStreamWaitEvent(stream, h->dE_done[e2], 0));
+    }
+    const int64_t rows_valid = (V - v0 < vs_this) ? V - v0 : vs_this;
+    s.Crows = (const bf16*)C + v0 * D;
+    if (use_lists) {
+      s.tile_list = (const uint32_t*)(ws + plan.off_tile_list) + slab * (plan.Np / 256) * slab_tiles;
+      s.tile_count = (const uint32_t*)(ws + plan.off_tile_count) + slab;
+    }
+    if (sort) {
+      // the slab's rows of C, gathered in sorted order (its buffer was last read by the
+      // recompute and the dE product of the slab that used it before, both waited for above)
+      bf16* Cs = (bf16*)(ws + plan.off_Cs[b]);
+      CCE_HIP(launch_gather_rows((const bf16*)C, s.perm, (int)v0, (int)rows_valid, (int)D, Cs, stream));
+      s.Crows = Cs;
+    }
+    CCE_HIP(launch_bwd_recompute_mfma(c, s, cus, stream));
+    if (serial) {
+      CCE_HIP(launch_bwd_dC_mfma(c, s, out_dC, stream));
+      CCE_HIP(launch_bwd_dE_mfma(c, s, stream));
+      continue;
+    }
+    CCE_HIP(hipEventRecord(h->recomputed[e], stream));
+    // dC products of consecutive slabs write disjoint rows: they alternate between two
+    // streams so that the last, partly filled round of one overlaps the next one's start
+    const int dC_i = (slab & 1) ? 2 : 0;
+    hipStream_t dC_stream = h->product[dC_i], dE_stream = h->product[1];
+    // a helper stream's first work of the call waits for the caller's earlier work on `stream`
+    if (!forked[dC_i]) CCE_HIP(hipStreamWaitEvent(dC_stream, h->started, 0));
+    forked[dC_i] = true;
+    CCE_HIP(hipStreamWaitEvent(dC_stream, h->recomputed[e], 0));
+    CCE_HIP(launch_bwd_dC_mfma(c, s, out_dC, dC_stream));
+    CCE_HIP(hipEventRecord(h->dC_done[e], dC_stream));
+    // dEacc is read-modify-written slab after slab: stream order keeps that sequence
+    if (!forked[1]) CCE_HIP(hipStreamWaitEvent(dE_stream, h->started, 0));
+    forked[1] = true;
+    CCE_HIP(hipStreamWaitEvent(dE_stream, h->recomputed[e], 0));
+    CCE_HIP(launch_bwd_dE_mfma(c, s, dE_stream));
+    CCE_HIP(hipEventRecord(h->dE_done[e], dE_stream));
+  }
+  return CCE_OK;
+}
+
+}  // namespace
+
+extern "C" {
 
 int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_t N, int64_t D, int64_t V,
                     float softcap, int64_t ignore_index, const float* lse, const float* dLoss, void* out_dE,
@@ -517,149 +652,73 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
   c.filter_dE = (opts->flags & CCE_FILTER_DE) ? 1 : 0;
   c.filter_dC = (opts->flags & CCE_FILTER_DC) ? 1 : 0;
   c.stats = (FilterStats*)ws;
-  // the MFMA gradient products address E and a slab of C with 32-bit byte offsets
-  if (mfma &&
-      ((uint64_t)N * (uint64_t)D * 2 >= ((uint64_t)1 << 32) || (uint64_t)vs * (uint64_t)D * 2 >= ((uint64_t)1 << 32)))
-    return CCE_EUNSUPPORTED;
-  CCE_HIP(launch_clear_stats(c.stats, stream));
   float* dEacc = (float*)(ws + plan.off_dEacc);
 
   if (mfma) {
+    // ---- everything that can refuse the call, before the first launch
+    // the gradient products address E and a slab of C with 32-bit byte offsets
+    if ((uint64_t)N * (uint64_t)D * 2 >= ((uint64_t)1 << 32) || (uint64_t)vs * (uint64_t)D * 2 >= ((uint64_t)1 << 32))
+      return CCE_EUNSUPPORTED;
+    // a work-list entry packs the token tile and the slab-local vocabulary tile into 16 bits each,
+    // and the tile-flag kernel puts the token tiles into grid.y
+    if (lists_layout && (plan.Np / 256 > 65535 || vs / 256 > 65535)) return CCE_EUNSUPPORTED;
+    if (sort) {
+      size_t need = 0;
+      CCE_HIP(vocab_sort_temp_needed(V, &need));
+      if (need > plan.sort_temp_bytes) return CCE_EWORKSPACE;
+    }
     Helpers* h = nullptr;
     st = helpers_for_device(&h);
     if (st != CCE_OK) return st;
     std::lock_guard<std::mutex> lock(h->mutex);
-    BwdMfmaSlab s{};
-    s.Np = (int)plan.Np;
-    s.dEacc = dEacc;
-    s.ksplit = dE_ksplit(N, D);
-    s.dE_part_stride = N * D;
-    // a filtered contraction keeps its list of 64-wide steps in LDS; longer ones run unfiltered
-    if (plan.Np / 64 > kMaxFilteredKSteps) c.filter_dC = 0;
-    // helper work may not start before the caller's earlier work on `stream` (which may produce C)
-    CCE_HIP(hipEventRecord(h->started, stream));
-    if (compact) {
-      int* idx_w = (int*)(ws + plan.off_idx);
-      int* count_w = (int*)(ws + plan.off_count);
-      bf16* Ec = (bf16*)(ws + plan.off_Ec);
-      CCE_HIP(launch_compact_tokens(targets, (int)N, (int)V, ignore_index, idx_w, count_w, stream));
-      CCE_HIP(launch_gather_tokens((const bf16*)E, idx_w, count_w, (int)N, (int)D, Ec, stream));
-      c.E = Ec;              // the vocabulary sort below keeps using the caller's E (its key is a batch mean)
-      c.n_dev = count_w;
-      c.idx = idx_w;
+    bool forked[3] = {false, false, false};
+    int ksplit = 1;
+    const int* n_dev = nullptr;
+    const int* idx = nullptr;
+    st = enqueue_backward_mfma(c, plan, h, C, targets, lse, N, D, V, vs, sort, lists_layout, compact, E, out_dC, opts, ws,
+                               stream, forked, &ksplit, &n_dev, &idx);
+    // join every helper stream that got work back into the caller's stream, also after a failure half
+    // way (a capture must not be left with unjoined streams)
+    for (int i = 0; i < 3; ++i) {
+      if (!forked[i]) continue;
+      hipError_t e1 = hipEventRecord(h->joined[i], h->product[i]);
+      hipError_t e2 = e1 == hipSuccess ? hipStreamWaitEvent(stream, h->joined[i], 0) : e1;
+      if (e2 != hipSuccess && st == CCE_OK) st = hip_fail(e2, "joining a helper stream");
     }
-    if (sort) {
-      VocabSortParams v{};
-      v.E = (const bf16*)E; v.C = (const bf16*)C; v.targets = targets;
-      v.N = (int)N; v.D = (int)D; v.V = (int)V; v.ignore_index = ignore_index;
-      v.partial = (float*)(ws + plan.off_partial);
-      v.mean = (float*)(ws + plan.off_mean);
-      v.key = (float*)(ws + plan.off_key);
-      v.key_sorted = (float*)(ws + plan.off_key_sorted);
-      v.index = (int*)(ws + plan.off_index);
-      v.perm = (int*)(ws + plan.off_perm);
-      v.inverse = (int*)(ws + plan.off_inverse);
-      v.targets_sorted = (int64_t*)(ws + plan.off_targets);
-      v.temp = ws + plan.off_sort_temp;
-      v.temp_bytes = plan.sort_temp_bytes;
-      hipError_t se = launch_vocab_sort(v, stream);
-      if (se == hipErrorOutOfMemory) return CCE_EWORKSPACE;
-      CCE_HIP(se);
-      c.targets = v.targets_sorted;    // from here on the vocabulary is indexed by sorted position
-      s.perm = v.perm;
-    }
-    const bool use_lists = lists_layout && opts->block_max && c.filter_dE && c.filter_dC && c.eps > 0.f;
-    const int64_t slab_tiles = vs / 256;
-    if (use_lists) {
-      TileListParams t{};
-      t.block_max = (const uint16_t*)opts->block_max;
-      t.stride = (int)plan.Np;
-      t.targets = targets; t.lse = lse;
-      t.n_dev = c.n_dev; t.idx = c.idx;
-      t.N = (int)N; t.V = (int)V; t.ignore_index = ignore_index;
-      t.log_eps = logf(c.eps) - 0.02f;   // margin for the fp32 rounding of lse and of the recorded maxima
-      t.n_tiles = (int)(plan.Np / 256); t.v_tiles = (int)((V + 255) / 256);
-      t.slab_tiles = (int)slab_tiles;
-      t.slabs = (int)((t.v_tiles + slab_tiles - 1) / slab_tiles);
-      t.tile_flag = (uint8_t*)(ws + plan.off_tile_flag);
-      t.tile_list = (uint32_t*)(ws + plan.off_tile_list);
-      t.tile_count = (uint32_t*)(ws + plan.off_tile_count);
-      CCE_HIP(launch_tile_lists(t, stream));
-    }
+    if (st != CCE_OK) return st;   // outputs are undefined after a failure past the first launch
     const int64_t n_slabs = (round_up(V, 256) + vs - 1) / vs;
-    uint32_t* flags_all = (uint32_t*)(ws + plan.off_flags[0]);
-    CCE_HIP(launch_zero_flags(flags_all, n_slabs * (int64_t)plan.flag_region_words, stream));
-    int64_t slab = 0;
-    for (int64_t v0 = 0; v0 < V; v0 += vs, ++slab) {
-      const int b = (int)(slab % kSlabBuffers), e = (int)(slab % kEventRing);
-      const int64_t vs_this = (round_up(V - v0, 256) < vs) ? round_up(V - v0, 256) : vs;
-      s.v0 = (int)v0;
-      s.vs = (int)vs_this;
-      s.first = v0 == 0;
-      s.GZ = (bf16*)(ws + plan.off_GZ[b]);
-      s.flags_nv = flags_all + slab * (int64_t)plan.flag_region_words;
-      s.flags_vn = s.flags_nv + (plan.Np / 256) * (vs_this / 64);
-      if (slab >= kSlabBuffers) {
-        // this slab's buffers were last read by the products of slab - kSlabBuffers
-        const int e2 = (int)((slab - kSlabBuffers) % kEventRing);
-        CCE_HIP(hipStreamWaitEvent(stream, h->dC_done[e2], 0));
-        CCE_HIP(hipStreamWaitEvent(stream, h->dE_done[e2], 0));
-      }
-      const int64_t rows_valid = (V - v0 < vs_this) ? V - v0 : vs_this;
-      s.Crows = (const bf16*)C + v0 * D;
-      if (use_lists) {
-        s.tile_list = (const uint32_t*)(ws + plan.off_tile_list) + slab * (plan.Np / 256) * slab_tiles;
-        s.tile_count = (const uint32_t*)(ws + plan.off_tile_count) + slab;
-      }
-      if (sort) {
-        // the slab's rows of C, gathered in sorted order (its buffer was last read by the
-        // recompute and the dE product of the slab that used it before, both waited for above)
-        bf16* Cs = (bf16*)(ws + plan.off_Cs[b]);
-        CCE_HIP(launch_gather_rows((const bf16*)C, s.perm, (int)v0, (int)rows_valid, (int)D, Cs, stream));
-        s.Crows = Cs;
-      }
-      CCE_HIP(launch_bwd_recompute_mfma(c, s, stream));
-      CCE_HIP(hipEventRecord(h->recomputed[e], stream));
-      // dC products of consecutive slabs write disjoint rows: they alternate between two
-      // streams so that the last, partly filled round of one overlaps the next one's start
-      hipStream_t dC_stream = h->product[(slab & 1) ? 2 : 0];
-      const bool serial = (opts->flags & CCE_SINGLE_STREAM) != 0;
-      if (serial) { dC_stream = stream; }
-      hipStream_t dE_stream = serial ? stream : h->product[1];
-      CCE_HIP(hipStreamWaitEvent(dC_stream, h->recomputed[e], 0));
-      CCE_HIP(launch_bwd_dC_mfma(c, s, out_dC, dC_stream));
-      CCE_HIP(hipEventRecord(h->dC_done[e], dC_stream));
-      // dEacc is read-modify-written slab after slab: stream order keeps that sequence
-      if (slab == 0) CCE_HIP(hipStreamWaitEvent(dE_stream, h->started, 0));
-      CCE_HIP(hipStreamWaitEvent(dE_stream, h->recomputed[e], 0));
-      CCE_HIP(launch_bwd_dE_mfma(c, s, dE_stream));
-      CCE_HIP(hipEventRecord(h->dE_done[e], dE_stream));
-    }
-    // join: the last record on each helper stream covers everything enqueued on it
-    const int e_last = (int)((slab - 1) % kEventRing);
-    CCE_HIP(hipStreamWaitEvent(stream, h->dC_done[e_last], 0));
-    if (slab >= 2) CCE_HIP(hipStreamWaitEvent(stream, h->dC_done[(int)((slab - 2) % kEventRing)], 0));
-    CCE_HIP(hipStreamWaitEvent(stream, h->dE_done[e_last], 0));
-    CCE_HIP(launch_count_flags(flags_all, (int64_t)plan.flag_region_words, (int)n_slabs, (int)(plan.Np / 256), (int)vs,
-                               (int)V, c.stats, c.n_dev, stream));
-    CCE_HIP(launch_store_dE(dEacc, s.ksplit, out_dE, opts->dtype, N, D, c.idx, c.n_dev, stream));
+    CCE_HIP(launch_count_flags((const uint32_t*)(ws + plan.off_flags[0]), (int64_t)plan.flag_region_words, (int)n_slabs,
+                               (int)(plan.Np / 256), (int)vs, (int)V, c.stats, n_dev, stream));
+    CCE_HIP(launch_store_dE(dEacc, ksplit, out_dE, opts->dtype, N, D, idx, n_dev, stream));
     return CCE_OK;
-  } else {
-    BwdPlainSlab s{};
-    s.GZ = (float*)(ws + plan.off_GZ[0]);
-    s.dEacc = dEacc;
-    s.flags = (uint8_t*)(ws + plan.off_flags[0]);
-    for (int64_t v0 = 0; v0 < V; v0 += vs) {
-      const int64_t vs_this = (round_up(V - v0, 64) < vs) ? round_up(V - v0, 64) : vs;
-      s.v0 = (int)v0;
-      s.vs = (int)vs_this;
-      s.first = v0 == 0;
-      CCE_HIP(launch_bwd_gz_plain(c, s, stream));
-      CCE_HIP(launch_bwd_dC_plain(c, s, out_dC, stream));
-      CCE_HIP(launch_bwd_dE_plain(c, s, stream));
-    }
+  }
+  CCE_HIP(launch_clear_stats(c.stats, stream));
+  BwdPlainSlab s{};
+  s.GZ = (float*)(ws + plan.off_GZ[0]);
+  s.dEacc = dEacc;
+  s.flags = (uint8_t*)(ws + plan.off_flags[0]);
+  for (int64_t v0 = 0; v0 < V; v0 += vs) {
+    const int64_t vs_this = (round_up(V - v0, 64) < vs) ? round_up(V - v0, 64) : vs;
+    s.v0 = (int)v0;
+    s.vs = (int)vs_this;
+    s.first = v0 == 0;
+    CCE_HIP(launch_bwd_gz_plain(c, s, stream));
+    CCE_HIP(launch_bwd_dC_plain(c, s, out_dC, stream));
+    CCE_HIP(launch_bwd_dE_plain(c, s, stream));
   }
   CCE_HIP(launch_store_dE(dEacc, 1, out_dE, opts->dtype, N, D, nullptr, nullptr, stream));
+  return CCE_OK;
+}
+
+int cce_set_workspace(void* workspace, size_t workspace_bytes) {
+  if ((workspace == nullptr) != (workspace_bytes == 0)) return CCE_EINVAL;
+  if (workspace && !aligned(workspace, 256)) return CCE_EINVAL;
+  int dev = 0;
+  CCE_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return CCE_EUNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_lent_mutex);
+  g_lent[dev].ptr = workspace;
+  g_lent[dev].bytes = workspace_bytes;
   return CCE_OK;
 }
 
@@ -669,9 +728,11 @@ int cce_forward(const void* E, const void* C, const int64_t* targets, int64_t N,
   cce_default_opts(CCE_BF16, &o);
   int st = check_common(E, C, targets, N, D, V, softcap, &o);
   if (st != CCE_OK) return st;
-  o.workspace_bytes = cce_workspace_bytes(CCE_OP_FORWARD, N, D, V, &o);
-  st = owned_workspace(o.workspace_bytes, &o.workspace);
+  LentWorkspace w;
+  st = lent_workspace(&w);
   if (st != CCE_OK) return st;
+  o.workspace = w.ptr;
+  o.workspace_bytes = w.bytes;      // cce_forward_ex checks it against the exact requirement
   return cce_forward_ex(E, C, targets, N, D, V, softcap, ignore_index, out_loss, out_lse, &o);
 }
 
@@ -706,21 +767,38 @@ int cce_backward(const void* E, const void* C, const int64_t* targets, int64_t N
   cce_default_opts(CCE_BF16, &o);
   int st = check_common(E, C, targets, N, D, V, softcap, &o);
   if (st != CCE_OK) return st;
-  o.workspace_bytes = cce_workspace_bytes(CCE_OP_BACKWARD, N, D, V, &o);
-  st = owned_workspace(o.workspace_bytes, &o.workspace);
+  LentWorkspace w;
+  st = lent_workspace(&w);
   if (st != CCE_OK) return st;
+  o.workspace = w.ptr;
+  o.workspace_bytes = w.bytes;      // cce_backward_ex uses the widest slab that fits it
   return cce_backward_ex(E, C, targets, N, D, V, softcap, ignore_index, lse, dLoss, out_dE, out_dC, &o);
+}
+
+int cce_forward_target_stats(const void* workspace, void* stream, uint64_t* out_of_range) {
+  if (!out_of_range) return CCE_EINVAL;
+  if (!workspace) {
+    // the workspace lent to the plain entry points
+    LentWorkspace w;
+    int st = lent_workspace(&w);
+    if (st != CCE_OK) return st;
+    workspace = w.ptr;
+  }
+  ForwardStats host{};
+  CCE_HIP(hipMemcpyAsync(&host, workspace, sizeof(host), hipMemcpyDeviceToHost, (hipStream_t)stream));
+  CCE_HIP(hipStreamSynchronize((hipStream_t)stream));
+  *out_of_range = host.bad_targets;
+  return CCE_OK;
 }
 
 int cce_backward_filter_stats(const void* workspace, void* stream, uint64_t* blocks_total, uint64_t* blocks_kept) {
   if (!blocks_total || !blocks_kept) return CCE_EINVAL;
   if (!workspace) {
-    int dev = 0;
-    CCE_HIP(hipGetDevice(&dev));
-    if (dev < 0 || dev >= kMaxDevices) return CCE_EUNSUPPORTED;
-    std::lock_guard<std::mutex> lock(g_owned_mutex);
-    workspace = g_owned[dev].ptr;
-    if (!workspace) return CCE_EWORKSPACE;
+    // the workspace lent to the plain entry points
+    LentWorkspace w;
+    int st = lent_workspace(&w);
+    if (st != CCE_OK) return st;
+    workspace = w.ptr;
   }
   FilterStats host{};
   CCE_HIP(hipMemcpyAsync(&host, workspace, sizeof(host), hipMemcpyDeviceToHost, (hipStream_t)stream));

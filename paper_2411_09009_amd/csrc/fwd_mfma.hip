@@ -120,6 +120,7 @@ __global__ __launch_bounds__(kThreads) void fwd_lse_mfma_kernel(FwdMfmaParams p)
 
   TileCoords tc;
   tc.init();
+  if (p.bad_targets && blockIdx.x == 0 && threadIdx.x == 0) *p.bad_targets = 0ull;   // the finalize kernel counts into it
 
   // each XCD works on a compact rectangle of (token tile, vocabulary split) pairs, so that
   // its L2 sees every E slice and C slice from several workgroups at about the same time

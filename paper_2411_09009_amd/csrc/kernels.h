@@ -101,6 +101,7 @@ struct FwdMfmaParams {
   const int* n_dev;        // optional device count of tokens actually present in E (ignored tokens removed):
                            // the kernel then plans for that many tokens and the partial stride is that
                            // count rounded up to 256
+  unsigned long long* bad_targets;   // optional counter the finalize kernel adds to: workgroup 0 clears it here
   uint16_t* block_max;     // optional [ceil(V / 128), block_max_stride] bf16 bits: for every token the largest
                            // (soft-capped) logit within each 128-wide vocabulary block, rounded up; nullptr = off
   int block_max_stride;    // N rounded up to 256
@@ -116,6 +117,7 @@ struct FwdPlainParams {
   float softcap;
   LsePartial* partial;  // [splits, N]
   int splits, tiles_per_split;   // 64-wide vocabulary tiles
+  unsigned long long* bad_targets;   // optional counter the finalize kernel adds to: workgroup (0, 0) clears it here
 };
 hipError_t launch_fwd_lse_plain(const FwdPlainParams& p, hipStream_t stream);
 
@@ -137,8 +139,17 @@ struct FinalizeParams {
   // (targets and the outputs keep the caller's indexing); nullptr = all N tokens in place
   const int* n_dev;
   const int* idx;
+  // optional: number of targets that are neither ignore_index nor inside [0, V) (they are treated as
+  // ignored); cleared by the forward kernel that precedes this one.  nullptr when ignored tokens were
+  // removed: the compaction kernel has then counted them already.
+  unsigned long long* bad_targets;
 };
 hipError_t launch_finalize(const FinalizeParams& p, hipStream_t stream);
+
+// Counters kept at the start of the forward workspace.
+struct ForwardStats {
+  unsigned long long bad_targets;   // targets that are neither ignore_index nor inside [0, V)
+};
 
 // ---- backward -----------------------------------------------------------------
 // Filter counters kept at the start of the backward workspace.
@@ -207,7 +218,8 @@ struct TileListParams {
   uint32_t* tile_count;        // [slabs] out
 };
 hipError_t launch_tile_lists(const TileListParams& p, hipStream_t stream);
-hipError_t launch_bwd_recompute_mfma(const BwdCommon& c, const BwdMfmaSlab& s, hipStream_t stream);
+// cus: compute units of the device (one workgroup, or one share of the work list, per CU)
+hipError_t launch_bwd_recompute_mfma(const BwdCommon& c, const BwdMfmaSlab& s, int cus, hipStream_t stream);
 // Filter flags of the MFMA path: every slab has its own region of `region_words` words
 // ([Np/256, vs/64] then [vs/256, Np/64]); all are cleared once before the first slab and
 // counted once after the last.
@@ -248,6 +260,8 @@ struct VocabSortParams {
   size_t temp_bytes;
 };
 size_t vocab_sort_temp_bytes(int64_t V);
+// what the radix sort really asks for (a size query: nothing is launched)
+hipError_t vocab_sort_temp_needed(int64_t V, size_t* bytes);
 size_t vocab_sort_partial_bytes(int64_t D);
 hipError_t launch_vocab_sort(const VocabSortParams& p, hipStream_t stream);
 // out[r][:] = C[perm[p0 + r]][:], r < rows (D a multiple of 8)
@@ -259,9 +273,10 @@ hipError_t launch_store_dE(const float* dEacc, int parts, void* out_dE, int dtyp
                            const int* idx, const int* n_dev, hipStream_t stream);
 
 // ---- removing ignored tokens (Appendix B) ---------------------------------------
-// idx[k] = index of the k-th token whose target is valid (in order), *count = their number
+// idx[k] = index of the k-th token whose target is valid (in order), *count = their number;
+// *bad_targets (optional) = number of targets that are neither ignore_index nor inside [0, V)
 hipError_t launch_compact_tokens(const int64_t* targets, int N, int V, int64_t ignore_index, int* idx, int* count,
-                                 hipStream_t stream);
+                                 unsigned long long* bad_targets, hipStream_t stream);
 // out[k][:] = E[idx[k]][:] for k < *count (bf16, D a multiple of 8)
 hipError_t launch_gather_tokens(const bf16* E, const int* idx, const int* count, int N, int D, bf16* out,
                                 hipStream_t stream);

@@ -66,6 +66,7 @@ __global__ __launch_bounds__(kBlock) void fwd_lse_plain_kernel(FwdPlainParams p)
   const T* C = (const T*)p.C;
   const int n0 = blockIdx.x * kT, split = blockIdx.y;
   const int t = threadIdx.x, tx = t & 15, ty = t >> 4;
+  if (p.bad_targets && blockIdx.x == 0 && blockIdx.y == 0 && t == 0) *p.bad_targets = 0ull;
   const int vt0 = split * p.tiles_per_split;
   const int v_tiles = (p.V + kT - 1) / kT;
   const int vt1 = min(vt0 + p.tiles_per_split, v_tiles);
@@ -140,6 +141,7 @@ __global__ __launch_bounds__(kBlock) void finalize_kernel(FinalizeParams p) {
   if (lane == 0) {
     p.out_lse[o] = lse;
     p.out_loss[o] = valid ? lse - softcap_fn(dot, p.softcap) : 0.f;
+    if (p.bad_targets && !valid && tgt != p.ignore_index) atomicAdd(p.bad_targets, 1ull);   // integer count: order-free
   }
 }
 
@@ -289,21 +291,27 @@ __global__ void fill_kernel(T* __restrict__ p, int64_t count, T value) {
 // Appendix B: the tokens that carry a loss, in order.  One workgroup walks the batch.
 __global__ __launch_bounds__(1024) void compact_tokens_kernel(const int64_t* __restrict__ targets, int N, int V,
                                                               int64_t ignore_index, int* __restrict__ idx,
-                                                              int* __restrict__ count) {
+                                                              int* __restrict__ count,
+                                                              unsigned long long* __restrict__ bad_targets) {
   __shared__ int wave_count[16];
   __shared__ int base_s;
+  __shared__ int bad_s;
+  if (threadIdx.x == 0) bad_s = 0;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (threadIdx.x == 0) base_s = 0;
   __syncthreads();
   for (int i0 = 0; i0 < N; i0 += 1024) {
     const int i = i0 + threadIdx.x;
-    bool on = false;
+    bool on = false, bad = false;
     if (i < N) {
       const int64_t t = targets[i];
       on = t != ignore_index && t >= 0 && t < V;
+      bad = !on && t != ignore_index;
     }
     const uint64_t mask = __builtin_amdgcn_ballot_w64(on);
+    const uint64_t bad_mask = __builtin_amdgcn_ballot_w64(bad);
     if (lane == 0) wave_count[wave] = __builtin_popcountll(mask);
+    if (lane == 0 && bad_mask) atomicAdd(&bad_s, __builtin_popcountll(bad_mask));
     __syncthreads();
     int pos = base_s + __builtin_popcountll(mask & ((1ull << lane) - 1ull));
     for (int w = 0; w < wave; ++w) pos += wave_count[w];
@@ -316,7 +324,10 @@ __global__ __launch_bounds__(1024) void compact_tokens_kernel(const int64_t* __r
     }
     __syncthreads();
   }
-  if (threadIdx.x == 0) *count = base_s;
+  if (threadIdx.x == 0) {
+    *count = base_s;
+    if (bad_targets) *bad_targets = (unsigned long long)bad_s;
+  }
 }
 
 // out[k][:] = E[idx[k]][:] for k < *count, 16 bytes per lane
@@ -405,8 +416,9 @@ hipError_t launch_store_dE(const float* dEacc, int parts, void* out_dE, int dtyp
 }
 
 hipError_t launch_compact_tokens(const int64_t* targets, int N, int V, int64_t ignore_index, int* idx, int* count,
-                                 hipStream_t stream) {
-  hipLaunchKernelGGL(compact_tokens_kernel, dim3(1), dim3(1024), 0, stream, targets, N, V, ignore_index, idx, count);
+                                 unsigned long long* bad_targets, hipStream_t stream) {
+  hipLaunchKernelGGL(compact_tokens_kernel, dim3(1), dim3(1024), 0, stream, targets, N, V, ignore_index, idx, count,
+                     bad_targets);
   return hipGetLastError();
 }
 

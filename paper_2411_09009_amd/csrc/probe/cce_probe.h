@@ -1,7 +1,8 @@
 /*
- * cce_probe.h - measurement helpers exported by the same library.  They are not
- * part of the method: the benchmark uses them to state the bf16 MFMA rate this
- * GPU sustains and to scale the profiler's HBM byte counters.
+ * cce_probe.h - measurement helpers of the benchmark, built into their own shared
+ * object (libcce_probe.so), not into the product library.  They are not part of the
+ * method: bench.py uses them to state the bf16 MFMA rate this GPU sustains and to
+ * scale the profiler's HBM byte counters.
  * All pointers are DEVICE pointers; calls are asynchronous on `stream`
  * (hipStream_t, NULL = null stream) and return a hipError_t value (0 = success).
  */

@@ -96,6 +96,16 @@ size_t vocab_sort_temp_bytes(int64_t V) {
   return (size_t)V * 16 + (1u << 20);
 }
 
+hipError_t vocab_sort_temp_needed(int64_t V, size_t* bytes) {
+  const float* key = nullptr;
+  float* key_out = nullptr;
+  const int* val = nullptr;
+  int* val_out = nullptr;
+  *bytes = 0;
+  return rocprim::radix_sort_pairs_desc((void*)nullptr, *bytes, key, key_out, val, val_out, (size_t)V, 0u, 32u,
+                                        (hipStream_t) nullptr);
+}
+
 size_t vocab_sort_partial_bytes(int64_t D) { return (size_t)kMeanRowBlocks * (size_t)D * sizeof(float); }
 
 hipError_t launch_vocab_sort(const VocabSortParams& p, hipStream_t stream) {

@@ -32,7 +32,7 @@ from oracle import cce_oracle as O   # noqa: E402
 from workloads import CONFIGS, make  # noqa: E402
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-FULL = ["small_vocab", "gemma2_2b", "llama3_8b", "stress", "stress_peaked"]
+FULL = ["small_vocab", "gemma2_2b", "llama3_8b", "stress", "stress_peaked", "gemma2_9b", "qwen25_7b", "gemma2_2b_n1024"]
 
 
 def checksums(w):

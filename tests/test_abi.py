@@ -22,14 +22,47 @@ def declared_symbols():
     return sorted(names)
 
 
-def test_library_exports_every_declared_symbol():
+# The boundary: the two spec calls, their extended forms, the sizing / option / reporting helpers
+# they need, the registration that lends the plain calls their scratch, and the allocation-free forward.
+BOUNDARY = {"cce_forward", "cce_backward", "cce_forward_ex", "cce_backward_ex", "cce_workspace_bytes",
+            "cce_block_max_bytes", "cce_strerror", "cce_default_opts", "cce_filter_block",
+            "cce_backward_filter_stats", "cce_forward_target_stats", "cce_set_workspace",
+            "cce_forward_noalloc", "cce_noalloc_scratch_bytes"}
+
+
+def test_library_exports_exactly_the_declared_boundary():
+    import subprocess
     lib = L.load()
     names = declared_symbols()
-    assert {"cce_forward", "cce_backward", "cce_forward_ex", "cce_backward_ex", "cce_workspace_bytes",
-            "cce_strerror", "cce_default_opts", "cce_filter_block", "cce_backward_filter_stats",
-            "cce_probe_mfma", "cce_probe_copy"} <= set(names)
+    assert set(names) == BOUNDARY
     for n in names:
         assert hasattr(lib, n), n
+    # and nothing else with the library's prefix: measurement probes live in a shared object of their own
+    out = subprocess.run(["nm", "-D", "--defined-only", L.LIB_PATH], stdout=subprocess.PIPE, text=True, check=True).stdout
+    exported = {line.split()[-1] for line in out.splitlines() if line.split()[-1].startswith("cce_")}
+    assert exported == BOUNDARY, exported ^ BOUNDARY
+
+
+def test_the_library_never_allocates_frees_or_synchronises_the_device():
+    src = os.path.join(ROOT, "paper_2411_09009_amd", "csrc")
+    for f in sorted(os.listdir(src)):
+        path = os.path.join(src, f)
+        if os.path.isfile(path):
+            text = open(path).read()
+            for word in ("hipMalloc", "hipFree", "hipDeviceSynchronize", "hipHostMalloc", "hipMemset"):
+                assert word not in text, (f, word)
+
+
+def test_plain_entry_points_need_a_lent_workspace():
+    lib = L.load()
+    buf = (ctypes.c_char * 4096)()
+    p = (ctypes.addressof(buf) + 255) // 256 * 256
+    # argument errors first, nothing touches the device
+    assert lib.cce_forward(None, p, p, 4, 64, 8, 0.0, -100, p, p) == -1
+    assert lib.cce_backward(p, p, p, 4, 64, 8, -1.0, -100, p, p, p, p) == -1
+    assert lib.cce_set_workspace(p + 8, 1024) == -1          # misaligned
+    assert lib.cce_set_workspace(None, 1024) == -1           # pointer / size inconsistent
+    assert lib.cce_set_workspace(p, 0) == -1
 
 
 def test_binding_exposes_the_same_names():
@@ -52,7 +85,7 @@ def test_forward_workspace_is_linear_in_tokens_and_independent_of_vocabulary():
     b = L.cce_workspace_bytes(L.CCE_OP_FORWARD, 8192, 2304, 128000, o)
     c = L.cce_workspace_bytes(L.CCE_OP_FORWARD, 16384, 2304, 256000, o)
     assert a == b                          # no O(V) term
-    assert a <= 8192 * 8 * 8 + 256         # at most 8 (max, sum) pairs per token
+    assert a <= 8192 * 8 * 8 + 512         # at most 8 (max, sum) pairs per token, plus the counters
     assert c <= 2 * a + 256
     logits_bytes = 8192 * 256000 * 4
     assert a < logits_bytes / 10000

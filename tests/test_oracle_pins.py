@@ -277,14 +277,77 @@ def test_block_filter_sandwich():
     assert np.array_equal(onlyC[0], full[0]) and np.array_equal(onlyC[1], elem[1])
 
 
-def test_at_most_one_over_eps_significant_entries():
-    E, C, x, _ = rand_problem(18, N=16, D=8, V=6000, scale=0.3, ignore=())
+def _constructed_counts():
+    """A problem whose number of softmax entries >= 2^-12 is known exactly for every row.
+
+    E_i is a unit vector e_{r(i)} and column r of C holds log(50) in its first k_r rows and 0 below, so row i
+    of the logits has k_r entries log(50) and V - k_r zeros: softmax 50 / (50 k + V - k) for the former and
+    1 / (50 k + V - k) for the latter.  With V = 5000 the former are far above 2^-12 (0.0084 at k = 20) and
+    the latter below it (at most 1 / 5049 = 0.000198 < 0.000244), so the count is k_r."""
+    V, ks = 5000, [1, 2, 7, 20]
+    C = np.zeros((V, len(ks)))
+    for r, k in enumerate(ks):
+        C[:k, r] = math.log(50.0)
+    pattern = [0, 3, 1, 2, 2, 0, 3]
+    E = np.eye(len(ks))[pattern]
+    expect = np.array([ks[r] for r in pattern])
+    return E, C, expect
+
+
+def test_significant_entries_per_row_on_a_constructed_case_and_by_brute_force():
+    """Section 4.3: at most 1 / eps = 4096 softmax entries per token reach eps = 2^-12."""
+    E, C, expect = _constructed_counts()
+    x = np.zeros(len(E), dtype=np.int64)
     _, lse = O.forward(E, C, x, 0.0, IGN)
-    cnt = O.significant_entries_per_row(E, C, lse)
-    assert cnt.max() <= 4096 and cnt.min() >= 0
+    cnt = O.significant_entries_per_row(E, C, lse, row_chunk=3)          # several chunks and a ragged last one
+    assert np.array_equal(cnt, expect)
+    # another threshold moves the count as the closed form says: every entry is >= 1 / 6000
+    assert np.array_equal(O.significant_entries_per_row(E, C, lse, eps=1.0 / 6000), np.full(len(E), 5000))
+    # with a cap the logits become cap * tanh(log(50) / cap): still k entries far above the rest
+    _, lse_c = O.forward(E, C, x, 2.0, IGN)
+    assert np.array_equal(O.significant_entries_per_row(E, C, lse_c, softcap=2.0), expect)
+    # brute force with scalar arithmetic on a small random problem (math.exp, plain loops)
+    Er, Cr, xr, _ = rand_problem(18, N=9, D=6, V=300, scale=1.4, ignore=())
+    eps = 1.0 / 256
+    _, lse_r = O.forward(Er, Cr, xr, 0.0, IGN)
+    brute = []
+    for i in range(9):
+        z = [sum(Er[i, d] * Cr[j, d] for d in range(6)) for j in range(300)]
+        tot = math.fsum(math.exp(v) for v in z)
+        brute.append(sum(1 for v in z if math.exp(v) / tot >= eps))
+    got = O.significant_entries_per_row(Er, Cr, lse_r, eps=eps)
+    assert np.array_equal(got, np.array(brute)) and 0 < got.min() and got.max() < 300
+    assert got.max() <= 256                                              # the 1 / eps bound
     # uniform softmax over 6000 classes: every entry 1/6000 < 2^-12, none significant
-    cnt0 = O.significant_entries_per_row(E, np.zeros_like(C), np.full(16, math.log(6000)))
+    cnt0 = O.significant_entries_per_row(Er, np.zeros((6000, 6)), np.full(9, math.log(6000)))
     assert np.all(cnt0 == 0)
+    # and the bound of the paper at its own threshold on a wide random problem
+    Ew, Cw, xw, _ = rand_problem(19, N=16, D=8, V=6000, scale=0.3, ignore=())
+    _, lse_w = O.forward(Ew, Cw, xw, 0.0, IGN)
+    assert O.significant_entries_per_row(Ew, Cw, lse_w).max() <= 4096
+
+
+def test_planted_mistakes_in_the_entry_counter_are_caught(monkeypatch):
+    E, C, expect = _constructed_counts()
+    x = np.zeros(len(E), dtype=np.int64)
+    _, lse = O.forward(E, C, x, 0.0, IGN)
+
+    def pin_passes():
+        return bool(np.array_equal(O.significant_entries_per_row(E, C, lse, row_chunk=3), expect))
+
+    assert pin_passes()
+    orig_logits = O.logits
+    orig_count = np.count_nonzero
+    monkeypatch.setattr(O.np, "count_nonzero", lambda a, axis=None: orig_count(a, axis=axis) - 1)      # off by one
+    assert not pin_passes()
+    monkeypatch.setattr(O.np, "count_nonzero", orig_count)
+    monkeypatch.setattr(O.np, "count_nonzero", lambda a, axis=None: orig_count(a, axis=axis) * 0)      # returns zeros
+    assert not pin_passes()
+    monkeypatch.setattr(O.np, "count_nonzero", orig_count)
+    monkeypatch.setattr(O, "logits", lambda E_, C_, cap=0.0: -orig_logits(E_, C_, cap))                # wrong sign
+    assert not pin_passes()
+    monkeypatch.setattr(O, "logits", orig_logits)
+    assert pin_passes()
 
 
 # ------------------------------------------------------------------ paper values

@@ -14,12 +14,13 @@ import paper_2411_09009_amd as L
 from oracle import cce_oracle as O
 from workloads import make
 
-from gpu_util import dtype_code, f64, max_rel, rel_fro, run_backward, run_forward, to_device, workspace
+from gpu_util import dtype_code, f64, max_rel, max_row_err, rel_fro, run_backward, run_forward, to_device, workspace
 
 pytestmark = pytest.mark.gpu
 
 TOL_LOSS = 1e-3
 TOL_GRAD = 1e-2
+TOL_ROW = 1e-2      # every row of dE / dC on its own: ||delta row|| <= TOL_ROW * max(||row||, median row norm)
 
 
 def oracle_all(w, eps=0.0, mode="element"):
@@ -66,8 +67,10 @@ def test_backward_unfiltered_matches_oracle_mid(cce, name, N, D, V, kw):
     ref_loss, ref_lse = O.forward(w.E64(), w.C64(), w.targets, w.softcap, w.ignore_index)
     rdE, rdC = O.backward(w.E64(), w.C64(), w.targets, ref_lse, lam.astype(np.float64), w.softcap, w.ignore_index)
     eE, eC = rel_fro(f64(dE), rdE), rel_fro(f64(dC), rdC)
-    print("bwd %s N=%d D=%d V=%d: dE err %.2e dC err %.2e" % (name, N, D, V, eE, eC))
+    rE, rC = max_row_err(f64(dE), rdE), max_row_err(f64(dC), rdC)
+    print("bwd %s N=%d D=%d V=%d: dE err %.2e (worst row %.2e) dC err %.2e (worst row %.2e)" % (name, N, D, V, eE, rE, eC, rC))
     assert eE <= TOL_GRAD and eC <= TOL_GRAD
+    assert rE <= TOL_ROW and rC <= TOL_ROW
     assert np.all(f64(dE)[w.targets == w.ignore_index] == 0.0)
 
 
@@ -236,6 +239,7 @@ def test_tiny_config_fp32_full_parity(cce):
     eE, eC = rel_fro(f64(dE), rdE), rel_fro(f64(dC), rdC)
     print("tiny fp32: lse %.2e dE %.2e dC %.2e" % (max_rel(f64(lse), ref_lse), eE, eC))
     assert eE <= 1e-4 and eC <= 1e-4
+    assert max_row_err(f64(dE), rdE) <= 1e-4 and max_row_err(f64(dC), rdC) <= 1e-4
     # narrowest slab (many slabs) gives the same answer
     dE2, dC2, _ = run_backward(w, E, C, t, lse, dloss, op=L.CCE_OP_BACKWARD_MIN)
     assert rel_fro(f64(dE2), rdE) <= 1e-4 and rel_fro(f64(dC2), rdC) <= 1e-4
@@ -354,18 +358,59 @@ def test_results_are_bitwise_reproducible(cce):
     assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1]) and a[2] == b[2]
 
 
-def test_plain_entry_points_use_library_workspace(cce):
+def test_plain_entry_points_draw_on_the_lent_workspace(cce):
+    """cce_forward / cce_backward (the spec signatures) allocate nothing: their scratch is the
+    buffer registered with cce_set_workspace, and without one they refuse."""
     w = make("gemma2_2b", N=300, D=128, V=1000)
     E, C, t = to_device(w)
-    loss, lse = L.cce_forward(E, C, t, w.softcap, w.ignore_index)
     dloss = torch.from_numpy(w.mean_dloss()).cuda()
-    dE, dC = L.cce_backward(E, C, t, lse, dloss, w.softcap, w.ignore_index)
+    L.cce_set_workspace(None)
+    with pytest.raises(L.CceError) as ei:
+        L.cce_forward(E, C, t, w.softcap, w.ignore_index)
+    assert ei.value.status == -2
+    o = L.make_opts(L.CCE_BF16)
+    small = workspace(L.cce_workspace_bytes(L.CCE_OP_FORWARD, w.N, w.D, w.V, o))
+    L.cce_set_workspace(small)
+    loss, lse = L.cce_forward(E, C, t, w.softcap, w.ignore_index)
+    with pytest.raises(L.CceError) as ei:                    # enough for the forward, not for the backward
+        L.cce_backward(E, C, t, lse, dloss, w.softcap, w.ignore_index)
+    assert ei.value.status == -2
+    lent = workspace(L.cce_workspace_bytes(L.CCE_OP_BACKWARD, w.N, w.D, w.V, o))
+    L.cce_set_workspace(lent)
     torch.cuda.synchronize()
+    free0 = torch.cuda.mem_get_info()[0]
+    dE, dC = torch.empty_like(E), torch.empty_like(C)
+    L.cce_forward(E, C, t, w.softcap, w.ignore_index, out_loss=loss, out_lse=lse)
+    L.cce_backward(E, C, t, lse, dloss, w.softcap, w.ignore_index, out_dE=dE, out_dC=dC)
+    torch.cuda.synchronize()
+    assert torch.cuda.mem_get_info()[0] == free0             # the library allocated nothing on the device
     ref_loss, ref_lse, rdE, rdC = oracle_all(w)
     assert max_rel(f64(lse), ref_lse) <= TOL_LOSS and max_rel(f64(loss), ref_loss) <= TOL_LOSS
     assert rel_fro(f64(dE), rdE) <= TOL_GRAD and rel_fro(f64(dC), rdC) <= TOL_GRAD
     total, kept = L.cce_backward_filter_stats()
     assert total > 0
+    L.cce_set_workspace(None)
+
+
+@pytest.mark.parametrize("flags", [None, "compact", "plain"])
+def test_out_of_range_targets_are_ignored_and_counted(cce, flags):
+    w = make("small_vocab", N=700, D=128, V=900, ignore_frac=0.1)
+    bad = [3, 255, 256, 699]
+    w.targets[bad] = [900, -1, 1 << 40, -101]                 # none equals ignore_index (-100)
+    E, C, t = to_device(w)
+    fl = {None: None, "compact": L.CCE_FILTER_DE | L.CCE_FILTER_DC | L.CCE_COMPACT_IGNORED,
+          "plain": L.CCE_PLAIN_KERNELS}[flags]
+    o = L.make_opts(L.CCE_BF16, flags=fl)
+    ws = workspace(L.cce_workspace_bytes(L.CCE_OP_FORWARD, w.N, w.D, w.V, o))
+    o = L.make_opts(L.CCE_BF16, flags=fl, workspace=ws)
+    for expect in (4, 4, 0):                                  # the counter is per call, not cumulative
+        if expect == 0:
+            t[torch.tensor(bad).cuda()] = w.ignore_index
+            w.targets[bad] = w.ignore_index
+        loss, lse = L.cce_forward_ex(E, C, t, w.softcap, w.ignore_index, o)
+        assert L.cce_forward_target_stats(ws) == expect
+        ref_loss, _ = O.forward(w.E64(), w.C64(), w.targets, w.softcap, w.ignore_index)
+        assert max_rel(f64(loss), ref_loss) <= TOL_LOSS and torch.all(loss[torch.tensor(bad).cuda()] == 0)
 
 
 def test_calls_on_a_side_stream_and_under_graph_capture(cce):

@@ -1,9 +1,11 @@
-"""The five benchmark configurations and their seeded generator.
+"""The five benchmark configurations, three more model shapes, and their seeded generator.
 
 Shapes follow the models the paper measures (Table 1: Gemma-2-2B, N=8192,
-D=2304, |V|=256000; Table A3: Phi-3.5-mini D=3072 |V|=32064 and Mistral NeMo
-D=5120 |V|=131072; Table A4: Llama-3-8B |V|=128256).  The paper's real weights
-and Alpaca token batches are replaced by seeded distributions.
+D=2304, |V|=256000; Table A3: Phi-3.5-mini D=3072 |V|=32064, Mistral NeMo
+D=5120 |V|=131072, Gemma-2 9B D=3584 |V|=256000, Qwen-2.5 7B D=3584 |V|=152064;
+Table A4: Llama-3-8B |V|=128256; Fig. A1 / A2: smaller batches at the Gemma-2 2B
+shape).  The paper's real weights and Alpaca token batches are replaced by
+seeded distributions.
 
 Recipe (fixed here, identical for every consumer):
   rng   = numpy.random.default_rng(seed)
@@ -53,6 +55,10 @@ CONFIGS = {
     "stress": Spec("stress", 65536, 5120, 131072, "bf16", "rms", 0.02, "zipf", 0.0, 30.0, 5),
     "stress_peaked": Spec("stress_peaked", 65536, 5120, 131072, "bf16", "rms", 0.02, "zipf", 0.0, 30.0, 5,
                           peaked=True),
+    # further shapes of Table A3 and a small batch (Fig. A1 / A2), same distributions
+    "gemma2_9b": Spec("gemma2_9b", 8192, 3584, 256000, "bf16", "rms", 0.02, "zipf", 0.02, 30.0, 6),
+    "qwen25_7b": Spec("qwen25_7b", 8192, 3584, 152064, "bf16", "rms", 0.02, "zipf", 0.02, 0.0, 7),
+    "gemma2_2b_n1024": Spec("gemma2_2b_n1024", 1024, 2304, 256000, "bf16", "rms", 0.02, "zipf", 0.02, 30.0, 8),
 }
 
 
