@@ -13,6 +13,8 @@ bound) and the fp64 CPU oracle timed on a bounded sample of the same workload.
                                (CCE_SINGLE_STREAM) and prints a per-phase table in the shape of the paper's
                                Table A2; under `rocprofv3 --kernel-trace --stats` the same run gives the
                                per-kernel durations
+  python bench.py --accumulation  times the dense backward with dE's sum over slabs kept in fp32 (default), in bf16
+                               and in bf16 with Kahan compensation (Section 5), and prints their distance from the default
   python bench.py --compaction prints forward / backward times with 0 %, 2 % and 60 % of the tokens ignored,
                                with and without CCE_COMPACT_IGNORED (Appendix B, Table A1)
   python bench.py --configs    prints a markdown table over the five benchmark configurations (seeded
@@ -205,6 +207,37 @@ def breakdown(workload, iters):
         print("| %s | %.3f | %.3f |" % (label, serial, multi), flush=True)
 
 
+def accumulation_table(workload, iters):
+    """Section 5, "CCE" vs "CCE-Kahan": precision of the sum that lives in device memory."""
+    import torch
+    import paper_2411_09009_amd as L
+    from workloads import make
+    L.load()
+    dev = torch.device("cuda:0")
+    w = make(workload)
+    N, D, V = w.N, w.D, w.V
+    E, C, t, dl = _device_inputs(w, dev)
+    both = L.CCE_FILTER_DE | L.CCE_FILTER_DC
+    o0 = L.make_opts(L.CCE_BF16)
+    ws = torch.empty(L.cce_workspace_bytes(L.CCE_OP_FORWARD, N, D, V, o0), dtype=torch.uint8, device=dev)
+    wb = torch.empty(L.cce_workspace_bytes(L.CCE_OP_BACKWARD, N, D, V, o0), dtype=torch.uint8, device=dev)
+    loss, lse = torch.empty(N, device=dev), torch.empty(N, device=dev)
+    dE, dC = torch.empty_like(E), torch.empty_like(C)
+    L.cce_forward_ex(E, C, t, w.softcap, w.ignore_index, L.make_opts(L.CCE_BF16, workspace=ws), out_loss=loss, out_lse=lse)
+    print("| dE accumulator across slabs (%s) | dense backward ms | dE vs the fp32 accumulator's (rel. Frobenius) |" % workload)
+    print("|---|---|---|")
+    ref = None
+    for label, fl in (("fp32 (default)", 0), ("bf16 (CCE_ACCUM_BF16)", L.CCE_ACCUM_BF16),
+                      ("bf16 + Kahan (CCE_ACCUM_KAHAN)", L.CCE_ACCUM_KAHAN)):
+        ob = L.make_opts(L.CCE_BF16, flags=both | fl, filter_eps=0.0, workspace=wb)
+        ms = float(np.median(_timed_ms(
+            lambda: L.cce_backward_ex(E, C, t, lse, dl, w.softcap, w.ignore_index, ob, out_dE=dE, out_dC=dC), iters)))
+        if ref is None:
+            ref = dE.float().clone()
+        err = float((dE.float() - ref).norm() / ref.norm())
+        print("| %s | %.3f | %.2e |" % (label, ms, err), flush=True)
+
+
 def compaction_table(iters):
     """Appendix B / Table A1: ignored tokens removed before the work, at the Gemma-2 2B shape."""
     import torch
@@ -319,6 +352,7 @@ def main():
     ap.add_argument("--configs", action="store_true")
     ap.add_argument("--breakdown", action="store_true")
     ap.add_argument("--compaction", action="store_true")
+    ap.add_argument("--accumulation", action="store_true")
     ap.add_argument("--seeds", type=int, default=5,
                     help="after the timed steps, regenerate the inputs with this many seeds and time each "
                          "(the paper's Table 1 averages 5 seeds); 0 skips it")
@@ -335,6 +369,9 @@ def main():
         return
     if args.breakdown:
         breakdown(args.workload, max(args.steps, 3))
+        return
+    if args.accumulation:
+        accumulation_table(args.workload, max(args.steps // 2, 3))
         return
     if args.compaction:
         compaction_table(max(args.steps // 2, 3))

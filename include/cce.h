@@ -93,6 +93,16 @@ enum {
                                 backward spreads a slab's recompute and its two gradient products over
                                 helper streams (joined back before the call returns); this flag gives the
                                 plain sequence, slower, e.g. for per-kernel profiling. */
+  CCE_ACCUM_BF16 = 1u << 7,  /* backward: keep dE's running sum over vocabulary slabs in bf16 in device memory, rounded
+                                after every slab, instead of fp32.  This is the paper's own choice for its sums in
+                                global memory ("the final gradient floating point type", Section 5) and is offered to
+                                measure what it costs in accuracy: the error grows with the number of slabs.  dC is
+                                not affected (each of its rows is complete after one pass, there is no sum in device
+                                memory).  bf16 MFMA path only (CCE_EUNSUPPORTED otherwise).  Same workspace size. */
+  CCE_ACCUM_KAHAN = 1u << 8, /* backward: as CCE_ACCUM_BF16 (implied) with Kahan-compensated summation, the paper's
+                                "CCE-Kahan" (Section 5): a second bf16 array holds the rounding error of the running
+                                sum and is subtracted from the next slab's contribution.  Both arrays together take
+                                the bytes of the fp32 accumulator they replace. */
   CCE_SKIP_TILES = 1u << 4    /* forward: also record, in opts->block_max, the largest logit of every token
                                 within each 128-wide vocabulary block; backward (with both CCE_FILTER_* set
                                 and filter_eps > 0): do not even recompute the logit tiles in which that

@@ -19,6 +19,12 @@ Definitions followed (paper section / equation):
         dE = (G . dloss) C,   dC = (G . dloss)^T E.
   * Section 4.3 "Gradient filtering": entries (or whole blocks, Alg. 4's
     all(|G| < eps) test) below eps = 2^-12 are dropped before the two products.
+  * Section 5 (ablations "CCE" vs "CCE-Kahan"): the paper's kernels keep their
+    sums in global memory in the gradient's storage type (bf16), optionally
+    with Kahan-compensated summation.  round_to_bf16, accumulate_rounded and
+    backward_dE_slab_accumulated model exactly that for a sum over vocabulary
+    slabs, so that the library's accumulation variants have something to be
+    compared with beyond the exact gradient.
   * Table A2 names logit soft-capping; the paper gives no formula.  Reading
     used here: a = cap * tanh(z / cap), applied to every logit including the
     target's, with derivative 1 - (a/cap)^2 chained into the gradient.
@@ -203,3 +209,62 @@ def significant_entries_per_row(E, C, lse, softcap=0.0, eps=FILTER_EPS_BF16, row
         S = np.exp(logits(E[r0:r1], C64, softcap) - _as64(lse)[r0:r1, None])
         out[r0:r1] = np.count_nonzero(S >= eps, axis=1)
     return out
+
+
+def round_to_bf16(x):
+    """Nearest bfloat16 (8 significant bits, ties to even) of every float64 in x, returned as float64.
+
+    Rounded directly from float64 (no intermediate float32).  The exponent range of bfloat16 is not
+    modelled: it equals float32's and nothing on this path comes near its ends."""
+    x = np.asarray(x, dtype=np.float64)
+    m, e = np.frexp(x)                       # x = m * 2**e with 0.5 <= |m| < 1
+    return np.ldexp(np.rint(m * 256.0) / 256.0, e)   # rint: ties to even
+
+
+def accumulate_rounded(terms, mode="bf16"):
+    """Sum terms[0] + terms[1] + ... with the running sum kept in bf16 (Section 5).
+
+    mode "exact": plain float64 sum.
+    mode "bf16":  sum <- round_to_bf16(sum + term) after every term.
+    mode "kahan": Kahan's compensated summation with both the running sum and the compensation
+                  stored in bf16:  y = term - comp;  t = round(sum + y);  comp = round((t - sum) - y);  sum = t."""
+    terms = [np.asarray(t, dtype=np.float64) for t in terms]
+    total = np.zeros_like(terms[0])
+    comp = np.zeros_like(terms[0])
+    for term in terms:
+        if mode == "exact":
+            total = total + term
+        elif mode == "bf16":
+            total = round_to_bf16(total + term)
+        elif mode == "kahan":
+            y = term - comp
+            t = round_to_bf16(total + y)
+            comp = round_to_bf16((t - total) - y)
+            total = t
+        else:
+            raise ValueError(mode)
+    return total
+
+
+def backward_dE_slab_accumulated(E, C, targets, lse, dloss, slab_cols, mode="bf16", softcap=0.0,
+                                 ignore_index=-100):
+    """dE as a sum over vocabulary slabs of slab_cols entries, accumulated as accumulate_rounded does.
+
+    Slab s contributes sum_{j in slab} GZ_ij C_j (exact, float64); the contributions are then added in
+    slab order with the running sum in the chosen precision."""
+    E64, C64 = _as64(E), _as64(C)
+    V = C64.shape[0]
+    t = np.asarray(targets, dtype=np.int64)
+    ok = valid_mask(t, V, ignore_index)
+    lam = np.where(ok, _as64(dloss), 0.0)
+    lse = _as64(lse)
+    terms = []
+    for v0 in range(0, V, int(slab_cols)):
+        v1 = min(V, v0 + int(slab_cols))
+        A = logits(E64, C64[v0:v1], softcap)
+        G = np.exp(A - lse[:, None])
+        G[~ok] = 0.0
+        hit = np.nonzero(ok & (t >= v0) & (t < v1))[0]
+        G[hit, t[hit] - v0] -= 1.0
+        terms.append(grad_wrt_preactivation(A, G, lam, softcap) @ C64[v0:v1])
+    return accumulate_rounded(terms, mode)

@@ -11,6 +11,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libc
 
 CCE_BF16, CCE_F32 = 0, 1
 CCE_FILTER_DE, CCE_FILTER_DC, CCE_VOCAB_SORT, CCE_PLAIN_KERNELS, CCE_SKIP_TILES, CCE_COMPACT_IGNORED, CCE_SINGLE_STREAM = 1, 2, 4, 8, 16, 32, 64
+CCE_ACCUM_BF16, CCE_ACCUM_KAHAN = 128, 256
 CCE_OP_FORWARD, CCE_OP_BACKWARD, CCE_OP_BACKWARD_MIN, CCE_OP_BACKWARD_WIDE = 0, 1, 2, 3
 
 

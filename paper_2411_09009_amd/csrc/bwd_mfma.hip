@@ -83,6 +83,7 @@ __global__ __launch_bounds__(256) void tile_compact_kernel(TileListParams p) {
 }
 
 enum { kNoCap = 0, kCap = 1 };
+enum { kAccF32 = 0, kAccBf16 = 1, kAccBf16Kahan = 2 };
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 constexpr int kMaxKSteps = 2048;   // longest filtered contraction: 131072 / 64
@@ -321,7 +322,12 @@ __global__ __launch_bounds__(kThreads) void bwd_recompute_mfma_kernel(BwdCommon 
 // blocks; with FILTERED only the blocks whose flag (row tile_c of `flags`) is set.
 //   DC = false:  P = C slab [vs, D] (K-major), Q = GZ [Np, vs] rows,      c = token      -> dEacc[c][d] (+)= acc
 //   DC = true :  P = E [N, D] (K-major),       Q = GZ [Np, vs] (K-major), c = vocabulary -> dC[v0 + c][d] = bf16(acc)
-template <bool DC, bool FILTERED>
+// ACC (dE only): how the sum over vocabulary slabs is kept in device memory between launches:
+//   kAccF32        fp32 accumulator (this library's default)
+//   kAccBf16       bf16 accumulator: the running sum is rounded to the gradient's storage type after every
+//                  slab, as the paper's kernels do for their sums in global memory (Section 5)
+//   kAccBf16Kahan  bf16 accumulator plus a bf16 compensation term (the paper's "CCE-Kahan")
+template <bool DC, bool FILTERED, int ACC = kAccF32>
 __global__ __launch_bounds__(kThreads) void bwd_product_mfma_kernel(BwdCommon c, BwdMfmaSlab sl, bf16* out_dC,
                                                                     XcdMap map) {
   __shared__ __attribute__((aligned(1024))) char lds[kLdsBytes];
@@ -446,37 +452,86 @@ __global__ __launch_bounds__(kThreads) void bwd_product_mfma_kernel(BwdCommon c,
           }
       }
     } else if (col < c.N) {
-      float* row = sl.dEacc + (int64_t)part * sl.dE_part_stride + (int64_t)col * c.D + d_wave + 4 * (tc.lane >> 5);
-      if (!sl.first) {
-        // every read of the column is issued before the first is waited for: 16 loads in
-        // flight instead of one round trip to memory after the other
-        float4 old[kRB][4];
+      if constexpr (ACC == kAccF32) {
+        float* row = sl.dEacc + (int64_t)part * sl.dE_part_stride + (int64_t)col * c.D + d_wave + 4 * (tc.lane >> 5);
+        if (!sl.first) {
+          // every read of the column is issued before the first is waited for: 16 loads in
+          // flight instead of one round trip to memory after the other
+          float4 old[kRB][4];
+#pragma unroll
+          for (int rb = 0; rb < kRB; ++rb)
+            if (rb < rb_valid) {
+#pragma unroll
+              for (int g = 0; g < 4; ++g) old[rb][g] = *(const float4*)(row + rb * 32 + 8 * g);
+            }
+#pragma unroll
+          for (int rb = 0; rb < kRB; ++rb)
+            if (rb < rb_valid) {
+#pragma unroll
+              for (int g = 0; g < 4; ++g) {
+                acc[rb][cb][g * 4 + 0] += old[rb][g].x;
+                acc[rb][cb][g * 4 + 1] += old[rb][g].y;
+                acc[rb][cb][g * 4 + 2] += old[rb][g].z;
+                acc[rb][cb][g * 4 + 3] += old[rb][g].w;
+              }
+            }
+        }
 #pragma unroll
         for (int rb = 0; rb < kRB; ++rb)
           if (rb < rb_valid) {
 #pragma unroll
-            for (int g = 0; g < 4; ++g) old[rb][g] = *(const float4*)(row + rb * 32 + 8 * g);
+            for (int g = 0; g < 4; ++g)
+              *(float4*)(row + rb * 32 + 8 * g) = make_float4(acc[rb][cb][g * 4 + 0], acc[rb][cb][g * 4 + 1],
+                                                              acc[rb][cb][g * 4 + 2], acc[rb][cb][g * 4 + 3]);
+          }
+      } else {
+        // running sum kept in bf16 (+ bf16 compensation): element (part, token, d) of [ksplit, N, D], the
+        // compensation terms in a second array of the same shape right after it
+        bf16* sum_row = (bf16*)sl.dEacc + (int64_t)part * sl.dE_part_stride + (int64_t)col * c.D + d_wave + 4 * (tc.lane >> 5);
+        bf16* comp_row = sum_row + (int64_t)sl.ksplit * sl.dE_part_stride;
+        uint2 old_sum[kRB][4], old_comp[kRB][4];
+#pragma unroll
+        for (int rb = 0; rb < kRB; ++rb)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            old_sum[rb][g] = make_uint2(0u, 0u);
+            old_comp[rb][g] = make_uint2(0u, 0u);
+            if (!sl.first && rb < rb_valid) {
+              old_sum[rb][g] = *(const uint2*)(sum_row + rb * 32 + 8 * g);
+              if (ACC == kAccBf16Kahan) old_comp[rb][g] = *(const uint2*)(comp_row + rb * 32 + 8 * g);
+            }
           }
 #pragma unroll
         for (int rb = 0; rb < kRB; ++rb)
           if (rb < rb_valid) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-              acc[rb][cb][g * 4 + 0] += old[rb][g].x;
-              acc[rb][cb][g * 4 + 1] += old[rb][g].y;
-              acc[rb][cb][g * 4 + 2] += old[rb][g].z;
-              acc[rb][cb][g * 4 + 3] += old[rb][g].w;
+              const uint32_t sw[2] = {old_sum[rb][g].x, old_sum[rb][g].y}, cw[2] = {old_comp[rb][g].x, old_comp[rb][g].y};
+              float t[4], cn[4];
+#pragma unroll
+              for (int j = 0; j < 4; ++j) {
+                // bf16 -> fp32 is exact: the 16 bits become the upper half of the word
+                const float sum = __uint_as_float((j & 1) ? (sw[j >> 1] & 0xffff0000u) : (sw[j >> 1] << 16));
+                const float comp = __uint_as_float((j & 1) ? (cw[j >> 1] & 0xffff0000u) : (cw[j >> 1] << 16));
+                const float y = acc[rb][cb][g * 4 + j] - comp;            // comp = 0 without compensation
+                t[j] = (float)(bf16)(sum + y);                            // the new running sum, as it will be stored
+                cn[j] = (t[j] - sum) - y;                                 // what the rounding added
+              }
+              f32x2 lo = {t[0], t[1]}, hi = {t[2], t[3]};
+              uint2 packed;
+              packed.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
+              packed.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
+              *(uint2*)(sum_row + rb * 32 + 8 * g) = packed;
+              if (ACC == kAccBf16Kahan) {
+                f32x2 clo = {cn[0], cn[1]}, chi = {cn[2], cn[3]};
+                uint2 cp;
+                cp.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(clo, bf16x2));
+                cp.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(chi, bf16x2));
+                *(uint2*)(comp_row + rb * 32 + 8 * g) = cp;
+              }
             }
           }
       }
-#pragma unroll
-      for (int rb = 0; rb < kRB; ++rb)
-        if (rb < rb_valid) {
-#pragma unroll
-          for (int g = 0; g < 4; ++g)
-            *(float4*)(row + rb * 32 + 8 * g) = make_float4(acc[rb][cb][g * 4 + 0], acc[rb][cb][g * 4 + 1],
-                                                            acc[rb][cb][g * 4 + 2], acc[rb][cb][g * 4 + 3]);
-        }
     }
   }
 }
@@ -563,10 +618,13 @@ hipError_t launch_bwd_dE_mfma(const BwdCommon& c, const BwdMfmaSlab& s, hipStrea
   const int tiles_r = (c.D + kTileR - 1) / kTileR;
   const XcdMap map = make_xcd_map(tiles_r, (s.Np / kTileC) * s.ksplit);
   dim3 grid(xcd_map_grid(map));
-  if (c.filter_dE && c.eps > 0.f)
-    hipLaunchKernelGGL((bwd_product_mfma_kernel<false, true>), grid, dim3(kThreads), 0, stream, c, s, (bf16*)nullptr, map);
-  else
-    hipLaunchKernelGGL((bwd_product_mfma_kernel<false, false>), grid, dim3(kThreads), 0, stream, c, s, (bf16*)nullptr, map);
+  const bool filtered = c.filter_dE && c.eps > 0.f;
+#define CCE_LAUNCH_DE(F, A) \
+  hipLaunchKernelGGL((bwd_product_mfma_kernel<false, F, A>), grid, dim3(kThreads), 0, stream, c, s, (bf16*)nullptr, map)
+  if (s.acc_mode == kAccBf16Kahan) { if (filtered) CCE_LAUNCH_DE(true, kAccBf16Kahan); else CCE_LAUNCH_DE(false, kAccBf16Kahan); }
+  else if (s.acc_mode == kAccBf16) { if (filtered) CCE_LAUNCH_DE(true, kAccBf16); else CCE_LAUNCH_DE(false, kAccBf16); }
+  else { if (filtered) CCE_LAUNCH_DE(true, kAccF32); else CCE_LAUNCH_DE(false, kAccF32); }
+#undef CCE_LAUNCH_DE
   return hipGetLastError();
 }
 

@@ -148,7 +148,7 @@ int check_common(const void* E, const void* C, const int64_t* targets, int64_t N
   if (!o) return CCE_EINVAL;
   if (o->dtype != CCE_BF16 && o->dtype != CCE_F32) return CCE_EUNSUPPORTED;
   if (o->flags & ~(uint32_t)(CCE_FILTER_DE | CCE_FILTER_DC | CCE_VOCAB_SORT | CCE_PLAIN_KERNELS | CCE_SKIP_TILES |
-                            CCE_COMPACT_IGNORED | CCE_SINGLE_STREAM)) return CCE_EUNSUPPORTED;
+                            CCE_COMPACT_IGNORED | CCE_SINGLE_STREAM | CCE_ACCUM_BF16 | CCE_ACCUM_KAHAN)) return CCE_EUNSUPPORTED;
   if (!E || !C || !targets) return CCE_EINVAL;
   if (N <= 0 || D <= 0 || V <= 0) return CCE_EINVAL;
   if (N > (int64_t)0x7fff0000 || V > (int64_t)0x7fff0000 || D > (1 << 22)) return CCE_EINVAL;
@@ -504,6 +504,7 @@ int enqueue_backward_mfma(const BwdCommon& c0, const BwdPlan& plan, Helpers* h, 
   s.dEacc = (float*)(ws + plan.off_dEacc);
   s.ksplit = dE_ksplit(N, D);
   s.dE_part_stride = N * D;
+  s.acc_mode = (opts->flags & CCE_ACCUM_KAHAN) ? 2 : (opts->flags & CCE_ACCUM_BF16) ? 1 : 0;
   *ksplit_out = s.ksplit;
   const bool serial = (opts->flags & CCE_SINGLE_STREAM) != 0;
   // a filtered contraction keeps its list of 64-wide steps in LDS; longer ones (N > 131072) run unfiltered
@@ -633,6 +634,8 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
   const bool mfma = use_mfma(D, opts);
   const bool sort = (opts->flags & CCE_VOCAB_SORT) != 0;
   if (sort && !mfma) return CCE_EUNSUPPORTED;   // vocabulary sorting exists on the bf16 MFMA path only
+  const bool acc_bf16 = (opts->flags & (CCE_ACCUM_BF16 | CCE_ACCUM_KAHAN)) != 0;
+  if (acc_bf16 && !mfma) return CCE_EUNSUPPORTED;   // so do the bf16 accumulation variants
   if (!opts->workspace) return CCE_EWORKSPACE;
   // the workspace is laid out for work lists whenever the flag asks for them (as sized by
   // cce_workspace_bytes); they are used only when nothing but filtered products reads GZ
@@ -689,7 +692,7 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
     const int64_t n_slabs = (round_up(V, 256) + vs - 1) / vs;
     CCE_HIP(launch_count_flags((const uint32_t*)(ws + plan.off_flags[0]), (int64_t)plan.flag_region_words, (int)n_slabs,
                                (int)(plan.Np / 256), (int)vs, (int)V, c.stats, n_dev, stream));
-    CCE_HIP(launch_store_dE(dEacc, ksplit, out_dE, opts->dtype, N, D, idx, n_dev, stream));
+    CCE_HIP(launch_store_dE(dEacc, ksplit, out_dE, opts->dtype, N, D, idx, n_dev, acc_bf16, stream));
     return CCE_OK;
   }
   CCE_HIP(launch_clear_stats(c.stats, stream));
@@ -706,7 +709,7 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
     CCE_HIP(launch_bwd_dC_plain(c, s, out_dC, stream));
     CCE_HIP(launch_bwd_dE_plain(c, s, stream));
   }
-  CCE_HIP(launch_store_dE(dEacc, 1, out_dE, opts->dtype, N, D, nullptr, nullptr, stream));
+  CCE_HIP(launch_store_dE(dEacc, 1, out_dE, opts->dtype, N, D, nullptr, nullptr, false, stream));
   return CCE_OK;
 }
 

@@ -183,7 +183,9 @@ struct BwdCommon {
 struct BwdMfmaSlab {
   int v0, vs, Np;
   bf16* GZ;             // [Np, vs]  dloss * G * a'   (token-major; zero for tokens >= N and columns >= V)
-  float* dEacc;         // [ksplit, N, D]
+  float* dEacc;         // [ksplit, N, D] fp32; with acc_mode != 0: bf16 [ksplit, N, D] running sums followed by
+                        // bf16 [ksplit, N, D] compensation terms (the same bytes)
+  int acc_mode;         // 0: fp32 accumulator; 1: bf16 running sum; 2: bf16 running sum + Kahan compensation
   int ksplit;           // parts the dE product cuts a slab's K steps into (>= 1), one accumulator each
   int64_t dE_part_stride;   // N * D
   uint32_t* flags_nv;   // [Np/256, vs/64]  block (256 tokens x 64 vocab) has a significant entry
@@ -269,8 +271,9 @@ hipError_t launch_gather_rows(const bf16* C, const int* perm, int p0, int rows, 
 
 // Sum of the `parts` accumulators dEacc (fp32 [parts, N, D]) -> out_dE in the storage dtype.  With idx /
 // n_dev (ignored tokens removed) row k goes to row idx[k] of out_dE for k < *n_dev and every other row is zeroed.
+// acc_bf16: the accumulators hold bf16 running sums (BwdMfmaSlab::acc_mode != 0) instead of fp32.
 hipError_t launch_store_dE(const float* dEacc, int parts, void* out_dE, int dtype, int64_t N, int64_t D,
-                           const int* idx, const int* n_dev, hipStream_t stream);
+                           const int* idx, const int* n_dev, bool acc_bf16, hipStream_t stream);
 
 // ---- removing ignored tokens (Appendix B) ---------------------------------------
 // idx[k] = index of the k-th token whose target is valid (in order), *count = their number;

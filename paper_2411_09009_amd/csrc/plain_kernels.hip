@@ -255,28 +255,28 @@ __global__ __launch_bounds__(kBlock) void bwd_dC_plain_kernel(BwdCommon c, BwdPl
     }
 }
 
-template <typename T>
-__global__ void store_dE_kernel(const float* __restrict__ acc, int parts, T* __restrict__ out, int64_t count) {
+template <typename T, typename A>
+__global__ void store_dE_kernel(const A* __restrict__ acc, int parts, T* __restrict__ out, int64_t count) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (; i < count; i += stride) {
-    float v = acc[i];
-    for (int p = 1; p < parts; ++p) v += acc[(int64_t)p * count + i];   // fixed order
+    float v = to_f<A>(acc[i]);
+    for (int p = 1; p < parts; ++p) v += to_f<A>(acc[(int64_t)p * count + i]);   // fixed order
     out[i] = from_f<T>(v);
   }
 }
 
 // ignored tokens removed: row k of acc belongs to the caller's token idx[k]
-template <typename T>
-__global__ void scatter_dE_kernel(const float* __restrict__ acc, int parts, int64_t part_stride, T* __restrict__ out,
+template <typename T, typename A>
+__global__ void scatter_dE_kernel(const A* __restrict__ acc, int parts, int64_t part_stride, T* __restrict__ out,
                                   int64_t D, const int* __restrict__ idx, const int* __restrict__ n_dev) {
   const int64_t count = (int64_t)*n_dev * D;
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (; i < count; i += stride) {
     const int64_t k = i / D, d = i % D;
-    float v = acc[i];
-    for (int p = 1; p < parts; ++p) v += acc[(int64_t)p * part_stride + i];
+    float v = to_f<A>(acc[i]);
+    for (int p = 1; p < parts; ++p) v += to_f<A>(acc[(int64_t)p * part_stride + i]);
     out[(int64_t)idx[k] * D + d] = from_f<T>(v);
   }
 }
@@ -394,23 +394,33 @@ hipError_t launch_bwd_dC_plain(const BwdCommon& c, const BwdPlainSlab& s, void* 
 }
 
 hipError_t launch_store_dE(const float* dEacc, int parts, void* out_dE, int dtype, int64_t N, int64_t D,
-                           const int* idx, const int* n_dev, hipStream_t stream) {
+                           const int* idx, const int* n_dev, bool acc_bf16, hipStream_t stream) {
   const int64_t count = N * D;
   int blocks = (int)((count + 1023) / 1024);
   if (blocks > 4096) blocks = 4096;
   if (blocks < 1) blocks = 1;
-  if (idx) {
-    if (dtype == CCE_F32) {
-      hipLaunchKernelGGL(fill_kernel<float>, dim3(blocks), dim3(256), 0, stream, (float*)out_dE, count, 0.f);
-      hipLaunchKernelGGL(scatter_dE_kernel<float>, dim3(blocks), dim3(256), 0, stream, dEacc, parts, count, (float*)out_dE, D, idx, n_dev);
+  const dim3 g(blocks), b(256);
+  if (acc_bf16) {
+    // bf16 running sums exist on the bf16 MFMA path only
+    const bf16* acc = (const bf16*)dEacc;
+    if (idx) {
+      hipLaunchKernelGGL(fill_kernel<bf16>, g, b, 0, stream, (bf16*)out_dE, count, (bf16)0.f);
+      hipLaunchKernelGGL((scatter_dE_kernel<bf16, bf16>), g, b, 0, stream, acc, parts, count, (bf16*)out_dE, D, idx, n_dev);
     } else {
-      hipLaunchKernelGGL(fill_kernel<bf16>, dim3(blocks), dim3(256), 0, stream, (bf16*)out_dE, count, (bf16)0.f);
-      hipLaunchKernelGGL(scatter_dE_kernel<bf16>, dim3(blocks), dim3(256), 0, stream, dEacc, parts, count, (bf16*)out_dE, D, idx, n_dev);
+      hipLaunchKernelGGL((store_dE_kernel<bf16, bf16>), g, b, 0, stream, acc, parts, (bf16*)out_dE, count);
+    }
+  } else if (idx) {
+    if (dtype == CCE_F32) {
+      hipLaunchKernelGGL(fill_kernel<float>, g, b, 0, stream, (float*)out_dE, count, 0.f);
+      hipLaunchKernelGGL((scatter_dE_kernel<float, float>), g, b, 0, stream, dEacc, parts, count, (float*)out_dE, D, idx, n_dev);
+    } else {
+      hipLaunchKernelGGL(fill_kernel<bf16>, g, b, 0, stream, (bf16*)out_dE, count, (bf16)0.f);
+      hipLaunchKernelGGL((scatter_dE_kernel<bf16, float>), g, b, 0, stream, dEacc, parts, count, (bf16*)out_dE, D, idx, n_dev);
     }
   } else if (dtype == CCE_F32) {
-    hipLaunchKernelGGL(store_dE_kernel<float>, dim3(blocks), dim3(256), 0, stream, dEacc, parts, (float*)out_dE, count);
+    hipLaunchKernelGGL((store_dE_kernel<float, float>), g, b, 0, stream, dEacc, parts, (float*)out_dE, count);
   } else {
-    hipLaunchKernelGGL(store_dE_kernel<bf16>, dim3(blocks), dim3(256), 0, stream, dEacc, parts, (bf16*)out_dE, count);
+    hipLaunchKernelGGL((store_dE_kernel<bf16, float>), g, b, 0, stream, dEacc, parts, (bf16*)out_dE, count);
   }
   return hipGetLastError();
 }

@@ -259,6 +259,19 @@ def test_full_size_matches_stored_oracle(cce, name):
         del dEc, dCc
     del dE, dC
 
+    if name == "gemma2_2b":
+        print("accumulation variants of dE's sum over the %d slabs (Section 5) %s" % ((w.V + 6143) // 6144, name), flush=True)
+        both = L.CCE_FILTER_DE | L.CCE_FILTER_DC
+        for label, fl in (("bf16 running sum", L.CCE_ACCUM_BF16), ("bf16 + Kahan", L.CCE_ACCUM_KAHAN)):
+            dEa, dCa, _ = run_backward(w, E, C, t, lse, dloss, eps=0.0, flags=both | fl)
+            aE = rel_fro(rows_of(dEa, er), ref_dE)
+            print("  %s: stored dE rows err %.2e (fp32 accumulator %.2e)" % (label, aE, eE), flush=True)
+            assert aE <= (TOL_GRAD if fl == L.CCE_ACCUM_KAHAN else 3 * TOL_GRAD)
+            if fl == L.CCE_ACCUM_KAHAN:
+                assert aE <= 1.5 * eE + 1e-3
+            assert rel_fro(rows_of(dCa, vr), ref_dC) == eC          # dC is untouched by the flag
+            del dEa, dCa
+
     if name in ("gemma2_2b", "stress"):
         print("uncapped twin of %s: shift invariance and sum_j dC_j = 0 at full size" % name, flush=True)
         check_invariants_without_cap(w, E, C, t, dloss)

@@ -350,6 +350,60 @@ def test_planted_mistakes_in_the_entry_counter_are_caught(monkeypatch):
     assert pin_passes()
 
 
+# ------------------------------------------------- sums kept in bf16 (Section 5, "CCE" vs "CCE-Kahan")
+def test_round_to_bf16_against_ties_a_bit_level_rounding_and_torch():
+    # spacing in [1, 2) is 2^-7: exact ties go to the even mantissa
+    assert O.round_to_bf16(1.0 + 2.0 ** -8) == 1.0
+    assert O.round_to_bf16(1.0 + 3 * 2.0 ** -8) == 1.0 + 2.0 ** -6
+    assert O.round_to_bf16(1.0 + 2.0 ** -8 + 2.0 ** -30) == 1.0 + 2.0 ** -7      # just above the tie
+    assert O.round_to_bf16(-257.0) == -256.0 and O.round_to_bf16(259.0) == 260.0 and O.round_to_bf16(0.0) == 0.0
+    rng = np.random.default_rng(31)
+    x = (rng.standard_normal(20000) * np.exp(rng.uniform(-20, 20, 20000))).astype(np.float32)
+    from workloads import f32_to_bf16_bits
+    from workloads.configs import bf16_bits_to_f64
+    assert np.array_equal(O.round_to_bf16(x.astype(np.float64)), bf16_bits_to_f64(f32_to_bf16_bits(x)))
+    assert np.array_equal(O.round_to_bf16(x.astype(np.float64)), torch.tensor(x).to(torch.bfloat16).double().numpy())
+
+
+def test_accumulate_rounded_stalls_without_compensation_and_recovers_with_it():
+    ones = [np.ones(3)] * 300
+    assert np.array_equal(O.accumulate_rounded(ones, "exact"), np.full(3, 300.0))
+    # 256 + 1 is a tie between 256 and 258 and goes to 256: the bf16 running sum stops growing there
+    assert np.array_equal(O.accumulate_rounded(ones, "bf16"), np.full(3, 256.0))
+    # Kahan's compensation carries the lost units over: the result stays within one spacing (2) of the true sum
+    k = O.accumulate_rounded(ones, "kahan")
+    assert np.all(np.abs(k - 300.0) <= 2.0) and np.array_equal(k, O.round_to_bf16(k))
+    # a hand-checked sequence: 256, then three times 1
+    seq = [np.array([256.0]), np.array([1.0]), np.array([1.0]), np.array([1.0])]
+    assert O.accumulate_rounded(seq, "bf16")[0] == 256.0
+    assert O.accumulate_rounded(seq, "kahan")[0] == 260.0       # 256 ->256 (comp -1) -> 258 (comp 0) -> 260 (tie 259, comp 1)
+    # random terms: compensation beats plain rounding, both are exact to within the format
+    rng = np.random.default_rng(32)
+    terms = [rng.standard_normal(4000) for _ in range(64)]
+    exact = O.accumulate_rounded(terms, "exact")
+    e_b = np.linalg.norm(O.accumulate_rounded(terms, "bf16") - exact) / np.linalg.norm(exact)
+    e_k = np.linalg.norm(O.accumulate_rounded(terms, "kahan") - exact) / np.linalg.norm(exact)
+    e_1 = np.linalg.norm(O.round_to_bf16(exact) - exact) / np.linalg.norm(exact)
+    assert e_1 < e_k < 2.0 * e_1 and e_b > 2.0 * e_k
+
+
+def test_slab_accumulated_dE_reduces_to_the_plain_gradient():
+    E, C, x, lam = rand_problem(33, N=10, D=6, V=50, ignore=(4,))
+    for cap in (0.0, 2.5):
+        _, lse = O.forward(E, C, x, cap, IGN)
+        dE, _ = O.backward(E, C, x, lse, lam, cap, IGN)
+        for slab in (7, 16, 50, 64):      # ragged last slab, exact division, one slab, more than |V|
+            got = O.backward_dE_slab_accumulated(E, C, x, lse, lam, slab, "exact", cap, IGN)
+            assert np.allclose(got, dE, rtol=0, atol=1e-13)
+        one = O.backward_dE_slab_accumulated(E, C, x, lse, lam, 50, "bf16", cap, IGN)
+        assert np.array_equal(one, O.round_to_bf16(dE)) or np.allclose(one, O.round_to_bf16(dE), rtol=2.0 ** -7, atol=0)
+        many_b = O.backward_dE_slab_accumulated(E, C, x, lse, lam, 5, "bf16", cap, IGN)
+        many_k = O.backward_dE_slab_accumulated(E, C, x, lse, lam, 5, "kahan", cap, IGN)
+        n = np.linalg.norm(dE)
+        assert np.linalg.norm(many_k - dE) / n <= 2.0 ** -8 and np.linalg.norm(many_b - dE) / n <= 10 * 2.0 ** -8
+        assert np.all(many_b[4] == 0) and np.all(many_k[4] == 0)          # ignored token
+
+
 # ------------------------------------------------------------------ paper values
 def _paper_values():
     path = os.path.join(os.path.dirname(__file__), "golden", "paper_values.txt")

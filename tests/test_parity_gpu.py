@@ -227,6 +227,61 @@ def test_removing_ignored_tokens_changes_nothing_but_the_cost(cce, frac):
     assert torch.equal(dC4, dC5) and rel_fro(f64(dE4), f64(dE5)) <= 2e-3
 
 
+@pytest.mark.parametrize("name,N,D,V", [("small_vocab", 5120, 2304, 4000), ("gemma2_2b", 300, 192, 5000)])
+def test_accumulation_precision_variants(cce, name, N, D, V):
+    """Section 5 ("CCE" vs "CCE-Kahan"): dE's running sum over vocabulary slabs kept in bf16, with and
+    without Kahan compensation, against the exact gradient and against the oracle's model of that sum."""
+    w = make(name, N=N, D=D, V=V)
+    E, C, t = to_device(w)
+    _, lse = run_forward(w, E, C, t)
+    lam = w.mean_dloss()
+    dloss = torch.from_numpy(lam).cuda()
+    both = L.CCE_FILTER_DE | L.CCE_FILTER_DC
+    mn = L.CCE_OP_BACKWARD_MIN                                   # 256-wide slabs: as many roundings as possible
+    slabs = (V + 255) // 256
+    E64, C64 = w.E64(), w.C64()
+    _, ref_lse = O.forward(E64, C64, w.targets, w.softcap, w.ignore_index)
+    rdE, rdC = O.backward(E64, C64, w.targets, ref_lse, lam.astype(np.float64), w.softcap, w.ignore_index)
+    dE0, dC0, _ = run_backward(w, E, C, t, lse, dloss, eps=0.0, op=mn)
+    dE1, dC1, _ = run_backward(w, E, C, t, lse, dloss, eps=0.0, op=mn, flags=both | L.CCE_ACCUM_BF16)
+    dE2, dC2, _ = run_backward(w, E, C, t, lse, dloss, eps=0.0, op=mn, flags=both | L.CCE_ACCUM_KAHAN)
+    assert torch.equal(dC0, dC1) and torch.equal(dC0, dC2)       # dC has no sum in device memory
+    e0, e1, e2 = (rel_fro(f64(x), rdE) for x in (dE0, dE1, dE2))
+    m1 = O.backward_dE_slab_accumulated(E64, C64, w.targets, ref_lse, lam, 256, "bf16", w.softcap, w.ignore_index)
+    m2 = O.backward_dE_slab_accumulated(E64, C64, w.targets, ref_lse, lam, 256, "kahan", w.softcap, w.ignore_index)
+    o1, o2 = rel_fro(m1, rdE), rel_fro(m2, rdE)
+    print("accumulation %s, %d slabs: fp32 %.2e | bf16 %.2e (oracle model %.2e) | bf16 + Kahan %.2e (oracle model %.2e)"
+          % (name, slabs, e0, e1, o1, e2, o2))
+    # compensation brings the bf16 sum back to the fp32 accumulator's level; without it the error grows
+    assert e2 <= TOL_GRAD and e2 <= 1.5 * e0 + 1e-3
+    assert e1 > 1.5 * e2
+    if N * D >= 171 * 65536:
+        # Enough (token tile, D tile) pairs that every slab is one contraction (small batches cut it into parts
+        # with a running sum each): the kernels then reproduce the modelled sums, up to the rounding decisions
+        # that the bf16 rounding of GZ moves.
+        assert 0.6 * o1 <= e1 <= 1.6 * o1 + 1e-3
+        assert rel_fro(f64(dE1), m1) <= 2.0 * o1 + 3e-3 and rel_fro(f64(dE2), m2) <= TOL_GRAD
+    # one slab: one rounding of every sum either way
+    w1 = make(name, N=N, D=D, V=256)
+    E1, C1, t1 = to_device(w1)
+    _, lse1 = run_forward(w1, E1, C1, t1)
+    a, _, _ = run_backward(w1, E1, C1, t1, lse1, dloss, eps=0.0)
+    b, _, _ = run_backward(w1, E1, C1, t1, lse1, dloss, eps=0.0, flags=both | L.CCE_ACCUM_BF16)
+    c, _, _ = run_backward(w1, E1, C1, t1, lse1, dloss, eps=0.0, flags=both | L.CCE_ACCUM_KAHAN)
+    if N * D >= 171 * 65536:
+        assert torch.equal(a, b) and torch.equal(a, c)
+    else:
+        assert rel_fro(f64(b), f64(a)) <= 5e-3 and rel_fro(f64(c), f64(a)) <= 5e-3
+    # together with removing ignored tokens, filtering, and on the plain path (refused)
+    d0, _, _ = run_backward(w, E, C, t, lse, dloss, op=mn, flags=both | L.CCE_ACCUM_KAHAN | L.CCE_COMPACT_IGNORED)
+    d1, _, _ = run_backward(w, E, C, t, lse, dloss, op=mn, flags=both | L.CCE_ACCUM_KAHAN)
+    assert torch.equal(d0, d1)
+    o = L.make_opts(L.CCE_BF16, flags=L.CCE_ACCUM_BF16 | L.CCE_PLAIN_KERNELS, workspace=workspace(1 << 26))
+    with pytest.raises(L.CceError) as ei:
+        L.cce_backward_ex(E, C, t, lse, dloss, w.softcap, w.ignore_index, o)
+    assert ei.value.status == -3
+
+
 def test_tiny_config_fp32_full_parity(cce):
     """Config 1 (N=256, D=64, V=1024, fp32, 5% ignored): the oracle covers every output."""
     w = make("tiny")

@@ -40,13 +40,13 @@ def draw(k):
     ign = float(rng.choice([0.0, 0.02, 0.5, 0.97]))
     flags = 0
     for bit, p in ((L.CCE_FILTER_DE, 0.8), (L.CCE_FILTER_DC, 0.8), (L.CCE_VOCAB_SORT, 0.3), (L.CCE_SKIP_TILES, 0.4),
-                   (L.CCE_COMPACT_IGNORED, 0.4), (L.CCE_SINGLE_STREAM, 0.2)):
+                   (L.CCE_COMPACT_IGNORED, 0.4), (L.CCE_SINGLE_STREAM, 0.2), (L.CCE_ACCUM_KAHAN, 0.15)):
         if rng.random() < p:
             flags |= bit
     op = int(rng.choice([L.CCE_OP_BACKWARD, L.CCE_OP_BACKWARD_MIN, L.CCE_OP_BACKWARD_WIDE]))
     eps = float(rng.choice([0.0, 2.0 ** -12]))
     if name == "tiny" or D % 64:
-        flags &= ~L.CCE_VOCAB_SORT          # the sorted walk exists on the MFMA path only
+        flags &= ~(L.CCE_VOCAB_SORT | L.CCE_ACCUM_KAHAN)   # the sorted walk and the bf16 sums exist on the MFMA path only
     if name == "tiny":
         eps = 0.0                           # the filter threshold is a bf16 notion (Section 4.3)
     return name, N, D, V, cap, ign, flags, op, eps
