@@ -335,13 +335,26 @@ __global__ __launch_bounds__(kThreads) void bwd_product_mfma_kernel(BwdCommon c,
   __shared__ int kcount_s;
   TileCoords tc;
   tc.init();
-  if (c.n_dev) c.N = *c.n_dev;   // ignored tokens removed: E and GZ hold this many tokens
+  // dE of a small batch has fewer tiles than CUs: the slab's K steps are then cut into ksplit
+  // parts, each with its own running sum (added up when dE is stored)
+  int ksplit = sl.ksplit;
+  int64_t part_stride = sl.dE_part_stride;
+  if (c.n_dev) {
+    // ignored tokens removed: E and GZ hold this many tokens, and the dE product is planned again for them
+    const int n_all = c.N;
+    c.N = *c.n_dev;
+    if (!DC) {
+      if (c.N <= 0) return;   // no token present: dE is zeroed when it is stored (dC still writes its zeros below)
+      const DEParts pp = dE_parts_present(c.N, n_all, c.D, sl.ksplit);
+      ksplit = pp.parts;
+      part_stride = pp.stride;
+      map = make_xcd_map(map.dim_a, ((c.N + kTileC - 1) / kTileC) * ksplit);
+    }
+  }
   int tile_r, tile_c;   // a = 256-wide slice of D, b = token tile x part of the slab (dE) or vocabulary tile (dC)
   if (!xcd_map_decode(map, blockIdx.x, tile_r, tile_c)) return;
-  // dE of a small batch has fewer tiles than CUs: the slab's K steps are then cut into ksplit
-  // parts, each with its own fp32 accumulator (summed when dE is stored)
-  const int part = DC ? 0 : tile_c % sl.ksplit;
-  if (!DC) tile_c /= sl.ksplit;
+  const int part = DC ? 0 : tile_c % ksplit;
+  if (!DC) tile_c /= ksplit;
   const int d0 = tile_r * kTileR, c0 = tile_c * kTileC;
   if (!DC && c0 >= c.N) return;   // a token tile past the tokens present
   // token tiles past the tokens present were not recomputed: the contraction over tokens stops before them
@@ -355,7 +368,7 @@ __global__ __launch_bounds__(kThreads) void bwd_product_mfma_kernel(BwdCommon c,
                                                                      // (the matching GZ entries are zero)
   const char* Q = (const char*)sl.GZ + (DC ? (int64_t)c0 * 2 : (int64_t)c0 * ldQ);
   const int ksteps = K / kTileK;
-  const int steps_per_part = DC ? ksteps : (ksteps + sl.ksplit - 1) / sl.ksplit;
+  const int steps_per_part = DC ? ksteps : (ksteps + ksplit - 1) / ksplit;
   const int k_lo = min(ksteps, part * steps_per_part), k_hi = min(ksteps, k_lo + steps_per_part);
 
   int kcount = k_hi - k_lo;
@@ -453,7 +466,7 @@ __global__ __launch_bounds__(kThreads) void bwd_product_mfma_kernel(BwdCommon c,
       }
     } else if (col < c.N) {
       if constexpr (ACC == kAccF32) {
-        float* row = sl.dEacc + (int64_t)part * sl.dE_part_stride + (int64_t)col * c.D + d_wave + 4 * (tc.lane >> 5);
+        float* row = sl.dEacc + (int64_t)part * part_stride + (int64_t)col * c.D + d_wave + 4 * (tc.lane >> 5);
         if (!sl.first) {
           // every read of the column is issued before the first is waited for: 16 loads in
           // flight instead of one round trip to memory after the other
@@ -487,8 +500,8 @@ __global__ __launch_bounds__(kThreads) void bwd_product_mfma_kernel(BwdCommon c,
       } else {
         // running sum kept in bf16 (+ bf16 compensation): element (part, token, d) of [ksplit, N, D], the
         // compensation terms in a second array of the same shape right after it
-        bf16* sum_row = (bf16*)sl.dEacc + (int64_t)part * sl.dE_part_stride + (int64_t)col * c.D + d_wave + 4 * (tc.lane >> 5);
-        bf16* comp_row = sum_row + (int64_t)sl.ksplit * sl.dE_part_stride;
+        bf16* sum_row = (bf16*)sl.dEacc + (int64_t)part * part_stride + (int64_t)col * c.D + d_wave + 4 * (tc.lane >> 5);
+        bf16* comp_row = sum_row + (int64_t)ksplit * part_stride;
         uint2 old_sum[kRB][4], old_comp[kRB][4];
 #pragma unroll
         for (int rb = 0; rb < kRB; ++rb)
@@ -617,7 +630,14 @@ hipError_t launch_count_flags(const uint32_t* flags, int64_t region_words, int s
 hipError_t launch_bwd_dE_mfma(const BwdCommon& c, const BwdMfmaSlab& s, hipStream_t stream) {
   const int tiles_r = (c.D + kTileR - 1) / kTileR;
   const XcdMap map = make_xcd_map(tiles_r, (s.Np / kTileC) * s.ksplit);
-  dim3 grid(xcd_map_grid(map));
+  unsigned wgs = xcd_map_grid(map);
+  if (c.n_dev) {
+    // the device plans again for the tokens present: t tiles cut into k(t) <= (256 + t / 2) / t parts make
+    // at most 256 + t / 2 workgroups while k >= 2 (t <= 170), and t workgroups otherwise
+    const unsigned most = (unsigned)((256 + 85 + kXcds - 1) / kXcds * kXcds + kXcds);
+    if (wgs < most) wgs = most;
+  }
+  dim3 grid(wgs);
   const bool filtered = c.filter_dE && c.eps > 0.f;
 #define CCE_LAUNCH_DE(F, A) \
   hipLaunchKernelGGL((bwd_product_mfma_kernel<false, F, A>), grid, dim3(kThreads), 0, stream, c, s, (bf16*)nullptr, map)

@@ -222,15 +222,7 @@ FwdPlan plan_forward(int64_t N, int64_t D, int64_t V, const cce_opts* o) {
 }
 
 // ------------------------------------------------------------------ backward plan
-// Small batches: the dE product then has fewer (token tile, D tile) pairs than CUs, and cuts each
-// slab's contraction into this many parts with an accumulator each.
-int dE_ksplit(int64_t N, int64_t D) {
-  const int64_t tiles = (round_up(N, 256) / 256) * (round_up(D, 256) / 256);
-  int64_t k = (256 + tiles / 2) / tiles;
-  if (k < 1) k = 1;
-  if (k > 8) k = 8;
-  return (int)k;
-}
+int dE_ksplit(int64_t N, int64_t D) { return dE_ksplit_for(N, D); }
 
 
 struct BwdPlan {

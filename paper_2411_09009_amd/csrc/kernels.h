@@ -87,6 +87,37 @@ inline size_t split_plan_max_partial_rows(int n_tokens, int v_tiles, int want_wg
   return (size_t)split_plan_max_grid(n_tokens, v_tiles, want_wgs, round_cap) * 256;
 }
 
+// Small batches leave the dE product with fewer (token tile, D tile) pairs than CUs; it then cuts each
+// slab's contraction into this many parts with a running sum each (added up when dE is stored).
+// Host and device: with ignored tokens removed the kernels plan again for the tokens present.
+__host__ __device__ inline int dE_ksplit_for(int64_t n_tokens, int64_t D) {
+  const int64_t tiles = ((n_tokens + 255) / 256) * ((D + 255) / 256);
+  if (tiles <= 0) return 1;
+  int64_t k = (256 + tiles / 2) / tiles;
+  if (k < 1) k = 1;
+  if (k > 8) k = 8;
+  return (int)k;
+}
+// Parts and part stride (elements) of the dE running sums when `n_tokens` of the `N` tokens the workspace
+// was sized for are present: the parts planned for n_tokens, as many of them as fit the space of the
+// ksplit_N parts of N rows, each part n_tokens rounded up to 256 rows.
+struct DEParts {
+  int parts;
+  int64_t stride;
+};
+__host__ __device__ inline DEParts dE_parts_present(int64_t n_tokens, int64_t N, int64_t D, int ksplit_N) {
+  DEParts p;
+  const int64_t rows = (n_tokens + 255) / 256 * 256;
+  int64_t k = dE_ksplit_for(n_tokens, D);
+  const int64_t fit = rows > 0 ? ((int64_t)ksplit_N * N) / rows : 1;
+  if (k > fit) k = fit;
+  if (k < 1) k = 1;
+  p.parts = (int)k;
+  p.stride = rows * D;
+  if (k == 1 && rows > N) p.stride = N * D;   // a single part never needs the padding rows
+  return p;
+}
+
 // ---- forward, MFMA path ------------------------------------------------------
 struct FwdMfmaParams {
   const bf16* E;        // [N, D]
@@ -188,6 +219,7 @@ struct BwdMfmaSlab {
   int acc_mode;         // 0: fp32 accumulator; 1: bf16 running sum; 2: bf16 running sum + Kahan compensation
   int ksplit;           // parts the dE product cuts a slab's K steps into (>= 1), one accumulator each
   int64_t dE_part_stride;   // N * D
+                        // (with BwdCommon::n_dev both are planned again on the device: dE_parts_present)
   uint32_t* flags_nv;   // [Np/256, vs/64]  block (256 tokens x 64 vocab) has a significant entry
   uint32_t* flags_vn;   // [vs/256, Np/64]  block (64 tokens x 256 vocab) has a significant entry
   int first;            // first slab of the call: dEacc is overwritten instead of added to
@@ -274,6 +306,7 @@ hipError_t launch_gather_rows(const bf16* C, const int* perm, int p0, int rows, 
 // acc_bf16: the accumulators hold bf16 running sums (BwdMfmaSlab::acc_mode != 0) instead of fp32.
 hipError_t launch_store_dE(const float* dEacc, int parts, void* out_dE, int dtype, int64_t N, int64_t D,
                            const int* idx, const int* n_dev, bool acc_bf16, hipStream_t stream);
+// (with idx / n_dev, `parts` is the count planned for N tokens; the kernel uses dE_parts_present)
 
 // ---- removing ignored tokens (Appendix B) ---------------------------------------
 // idx[k] = index of the k-th token whose target is valid (in order), *count = their number;

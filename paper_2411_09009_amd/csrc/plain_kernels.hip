@@ -267,10 +267,14 @@ __global__ void store_dE_kernel(const A* __restrict__ acc, int parts, T* __restr
 }
 
 // ignored tokens removed: row k of acc belongs to the caller's token idx[k]
+// (`parts` running sums were planned for the N tokens of the call; the kernels planned again for the tokens present)
 template <typename T, typename A>
-__global__ void scatter_dE_kernel(const A* __restrict__ acc, int parts, int64_t part_stride, T* __restrict__ out,
+__global__ void scatter_dE_kernel(const A* __restrict__ acc, int parts, int64_t N, T* __restrict__ out,
                                   int64_t D, const int* __restrict__ idx, const int* __restrict__ n_dev) {
   const int64_t count = (int64_t)*n_dev * D;
+  const DEParts pp = dE_parts_present(*n_dev, N, D, parts);
+  parts = pp.parts;
+  const int64_t part_stride = pp.stride;
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (; i < count; i += stride) {
@@ -405,17 +409,17 @@ hipError_t launch_store_dE(const float* dEacc, int parts, void* out_dE, int dtyp
     const bf16* acc = (const bf16*)dEacc;
     if (idx) {
       hipLaunchKernelGGL(fill_kernel<bf16>, g, b, 0, stream, (bf16*)out_dE, count, (bf16)0.f);
-      hipLaunchKernelGGL((scatter_dE_kernel<bf16, bf16>), g, b, 0, stream, acc, parts, count, (bf16*)out_dE, D, idx, n_dev);
+      hipLaunchKernelGGL((scatter_dE_kernel<bf16, bf16>), g, b, 0, stream, acc, parts, N, (bf16*)out_dE, D, idx, n_dev);
     } else {
       hipLaunchKernelGGL((store_dE_kernel<bf16, bf16>), g, b, 0, stream, acc, parts, (bf16*)out_dE, count);
     }
   } else if (idx) {
     if (dtype == CCE_F32) {
       hipLaunchKernelGGL(fill_kernel<float>, g, b, 0, stream, (float*)out_dE, count, 0.f);
-      hipLaunchKernelGGL((scatter_dE_kernel<float, float>), g, b, 0, stream, dEacc, parts, count, (float*)out_dE, D, idx, n_dev);
+      hipLaunchKernelGGL((scatter_dE_kernel<float, float>), g, b, 0, stream, dEacc, parts, N, (float*)out_dE, D, idx, n_dev);
     } else {
       hipLaunchKernelGGL(fill_kernel<bf16>, g, b, 0, stream, (bf16*)out_dE, count, (bf16)0.f);
-      hipLaunchKernelGGL((scatter_dE_kernel<bf16, float>), g, b, 0, stream, dEacc, parts, count, (bf16*)out_dE, D, idx, n_dev);
+      hipLaunchKernelGGL((scatter_dE_kernel<bf16, float>), g, b, 0, stream, dEacc, parts, N, (bf16*)out_dE, D, idx, n_dev);
     }
   } else if (dtype == CCE_F32) {
     hipLaunchKernelGGL((store_dE_kernel<float, float>), g, b, 0, stream, dEacc, parts, (float*)out_dE, count);

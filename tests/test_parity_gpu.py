@@ -205,7 +205,9 @@ def test_removing_ignored_tokens_changes_nothing_but_the_cost(cce, frac):
     for eps in (0.0, None):
         dE0, dC0, st0 = run_backward(w, E, C, t, lse0, dloss, eps=eps)
         dE1, dC1, st1 = run_backward(w, E, C, t, lse1, dloss, eps=eps, flags=both | cmp_)
-        assert torch.equal(dE0, dE1)                                  # rows of dE are per token
+        # rows of dE are per token; the contraction over a slab is cut into parts planned for the tokens
+        # present, so the fp32 sums may be taken in another order
+        assert rel_fro(f64(dE1), f64(dE0)) <= 2e-3 and max_row_err(f64(dE1), f64(dE0)) <= 4e-3
         assert torch.all(dE1[~valid] == 0)
         if frac < 1.0:
             assert rel_fro(f64(dC1), f64(dC0)) <= 2e-3                # other token order in the sums over tokens
@@ -275,7 +277,7 @@ def test_accumulation_precision_variants(cce, name, N, D, V):
     # together with removing ignored tokens, filtering, and on the plain path (refused)
     d0, _, _ = run_backward(w, E, C, t, lse, dloss, op=mn, flags=both | L.CCE_ACCUM_KAHAN | L.CCE_COMPACT_IGNORED)
     d1, _, _ = run_backward(w, E, C, t, lse, dloss, op=mn, flags=both | L.CCE_ACCUM_KAHAN)
-    assert torch.equal(d0, d1)
+    assert rel_fro(f64(d0), f64(d1)) <= 4e-3
     o = L.make_opts(L.CCE_BF16, flags=L.CCE_ACCUM_BF16 | L.CCE_PLAIN_KERNELS, workspace=workspace(1 << 26))
     with pytest.raises(L.CceError) as ei:
         L.cce_backward_ex(E, C, t, lse, dloss, w.softcap, w.ignore_index, o)
