@@ -15,6 +15,8 @@ bound) and the fp64 CPU oracle timed on a bounded sample of the same workload.
                                per-kernel durations
   python bench.py --accumulation  times the dense backward with dE's sum over slabs kept in fp32 (default), in bf16
                                and in bf16 with Kahan compensation (Section 5), and prints their distance from the default
+  python bench.py --probe      prints what the tile engine's activities (MFMA, LDS fragment reads, direct-to-LDS loads)
+                               cost on this GPU, on random and on all-zero operands
   python bench.py --compaction prints forward / backward times with 0 %, 2 % and 60 % of the tokens ignored,
                                with and without CCE_COMPACT_IGNORED (Appendix B, Table A1)
   python bench.py --configs    prints a markdown table over the five benchmark configurations (seeded
@@ -68,6 +70,8 @@ class Probes:
         lib.cce_probe_mfma.restype = ctypes.c_int
         lib.cce_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         lib.cce_probe_copy.restype = ctypes.c_int
+        lib.cce_probe_engine.argtypes = [vp, vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp]
+        lib.cce_probe_engine.restype = ctypes.c_int
         self.lib = lib
 
     def mfma(self, frags, out, blocks, iters):
@@ -76,11 +80,44 @@ class Probes:
                                      torch.cuda.current_stream().cuda_stream)
         assert rc == 0, "cce_probe_mfma: hipError_t %d" % rc
 
+    def engine(self, data, out, blocks, iters, lds_reads, dma):
+        import torch
+        assert data.numel() * data.element_size() >= (8 << 20) + 65536 and out.numel() >= blocks * 512
+        rc = self.lib.cce_probe_engine(data.data_ptr(), out.data_ptr(), int(blocks), int(iters), int(lds_reads), int(dma),
+                                       torch.cuda.current_stream().cuda_stream)
+        assert rc == 0, "cce_probe_engine: hipError_t %d" % rc
+
     def copy(self, dst, src):
         import torch
         rc = self.lib.cce_probe_copy(dst.data_ptr(), src.data_ptr(), src.numel() * src.element_size(),
                                      torch.cuda.current_stream().cuda_stream)
         assert rc == 0, "cce_probe_copy: hipError_t %d" % rc
+
+
+def probe_table():
+    """What each activity of the tile engine costs on this GPU: the register-resident MFMA loop alone, with LDS
+    fragment reads, with direct-to-LDS loads, on operands like E and C (N(0,1) and N(0, 0.02^2)) and on zeros."""
+    import torch
+    dev = torch.device("cuda:0")
+    probes = Probes()
+    n = ((8 << 20) + 65536) // 2
+    real = torch.randn(n, device=dev)
+    idx = (torch.arange(n, device=dev) // 16384) % 2 == 1          # alternate 32 KB of E-like and of C-like values
+    real = torch.where(idx, real * 0.02, real).to(torch.bfloat16)
+    out = torch.empty(512 * 512, dtype=torch.float32, device=dev)
+    blocks, iters = 512, 20000
+    flop = blocks * 8 * iters * 8 * 32768.0
+    print("| MFMA loop (v_mfma_f32_32x32x16_bf16, 8 waves per CU) | random operands TFLOP/s | all-zero operands TFLOP/s |")
+    print("|---|---|---|")
+    for label, reads, dma in (("alone", 0, 0), ("+ 4 ds_read_b128 per 8 MFMAs (a 128 x 128 wave tile's rate)", 4, 0),
+                              ("+ 6 ds_read_b128 per 8 MFMAs (the 128 x 64 wave tile's rate)", 6, 0),
+                              ("+ 6 reads + direct-to-LDS loads of a 256 x 256 x 64 stage (L2 hits)", 6, 1),
+                              ("+ 4 reads + the same loads", 4, 1)):
+        res = []
+        for data in (real, torch.zeros_like(real)):
+            ts = _timed_ms(lambda: probes.engine(data, out, blocks, iters, reads, dma), 3, 1)
+            res.append(flop / (min(ts) * 1e-3) / 1e12)
+        print("| %s | %.0f | %.0f |" % (label, res[0], res[1]), flush=True)
 
 
 def cpu_baseline(w, rows):
@@ -353,6 +390,7 @@ def main():
     ap.add_argument("--breakdown", action="store_true")
     ap.add_argument("--compaction", action="store_true")
     ap.add_argument("--accumulation", action="store_true")
+    ap.add_argument("--probe", action="store_true", help="table of what the tile engine's activities cost on this GPU")
     ap.add_argument("--seeds", type=int, default=5,
                     help="after the timed steps, regenerate the inputs with this many seeds and time each "
                          "(the paper's Table 1 averages 5 seeds); 0 skips it")
@@ -369,6 +407,9 @@ def main():
         return
     if args.breakdown:
         breakdown(args.workload, max(args.steps, 3))
+        return
+    if args.probe:
+        probe_table()
         return
     if args.accumulation:
         accumulation_table(args.workload, max(args.steps // 2, 3))
