@@ -156,12 +156,17 @@ def _device_inputs(w, dev):
     return E, C, t, dl
 
 
-def _timed_ms(fn, iters, warm=2):
-    """Per-call times in ms of `iters` calls, HIP events on the stream the library launches on."""
+def _timed_ms(fn, iters, warm=2, warm_seconds=0.3):
+    """Per-call times in ms of `iters` calls, HIP events on the stream the library launches on.
+    Warm-up: at least `warm` calls and at least `warm_seconds` of them (after seconds of host-side input
+    generation the GPU has clocked down; a couple of 1 ms calls do not bring it back)."""
     import torch
-    for _ in range(warm):
+    t0 = time.perf_counter()
+    k = 0
+    while k < warm or time.perf_counter() - t0 < warm_seconds:
         fn()
-    torch.cuda.synchronize()
+        torch.cuda.synchronize()
+        k += 1
     ts = []
     for _ in range(iters):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
