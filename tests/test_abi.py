@@ -182,3 +182,44 @@ def test_header_is_plain_c_and_the_library_links_from_c(tmp_path):
     r = subprocess.run([exe], stdout=subprocess.PIPE, text=True)
     assert r.returncode == 0, r.stdout
     assert r.stdout.startswith("forward ")
+
+
+def test_host_code_under_address_and_undefined_sanitizers(tmp_path):
+    """The dispatcher's host code (argument checks, workspace layouts, slab fitting) built with the address and
+    undefined-behaviour sanitizers (host side only: device code is compiled as usual) and driven by a C program
+    that sweeps shapes from 1 to the ABI's limits over every layout-changing flag.  No call reaches the GPU."""
+    import glob
+    import shutil
+    import subprocess
+    from paper_2411_09009_amd import build as B
+    clang = "/opt/rocm/lib/llvm/bin/clang"
+    rt = glob.glob("/opt/rocm/lib/llvm/lib/clang/*/lib/linux/libclang_rt.asan-x86_64.so")
+    if not (os.path.exists(B.HIPCC) and os.path.exists(clang) and rt):
+        pytest.skip("no ROCm clang with sanitizer runtimes")
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined"]
+    flags = [f for f in B.FLAGS if f != "-O3"] + ["-O1", "-g"]
+    objs = []
+    procs = []
+    for src in B.SOURCES:
+        obj = str(tmp_path / src.replace(".hip", ".o"))
+        objs.append(obj)
+        procs.append(subprocess.Popen([B.HIPCC, *flags, *san, "-c", os.path.join(B.CSRC, src), "-o", obj],
+                                      stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True))
+    for pr in procs:
+        out, _ = pr.communicate()
+        assert pr.returncode == 0, out
+    lib = str(tmp_path / "libcce_san.so")
+    subprocess.run([B.HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-fsanitize=address", "-fsanitize=undefined",
+                    "-shared-libsan", *objs, "-o", lib], check=True, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)
+    exe = str(tmp_path / "host_sweep")
+    subprocess.run([clang, "-std=c99", "-g", "-fsanitize=address", "-fsanitize=undefined", "-fno-sanitize-recover=undefined",
+                    "-shared-libsan", "-I", os.path.join(ROOT, "include"), os.path.join(ROOT, "tests", "abi_c", "host_sweep.c"),
+                    "-L", str(tmp_path), "-lcce_san", "-Wl,-rpath," + str(tmp_path), "-Wl,-rpath,/opt/rocm/lib",
+                    "-Wl,-rpath," + os.path.dirname(rt[0]), "-o", exe], check=True)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    r = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, env=env)
+    if r.returncode != 0 and "ASan runtime does not come first" in r.stdout:
+        pytest.skip("another preloaded library precedes the sanitizer runtime in this environment")
+    assert r.returncode == 0 and "host sweep ok" in r.stdout, r.stdout
+    shutil.rmtree(str(tmp_path), ignore_errors=True)
