@@ -235,7 +235,7 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets,
  * who keeps it alive and unused by anything else until it registers another buffer or NULL / 0
  * (which withdraws it).  Forward and backward calls share it, so calls that use it must not
  * overlap (one stream, or ordered by the caller).  cce_workspace_bytes(CCE_OP_BACKWARD, ...) of the
- * largest problem covers both.  The spec signatures carry no workspace argument and the
+ * largest problem covers both.  The plain signatures carry no workspace argument and the
  * library does not allocate: this call is how memory reaches them.  Host-side only (nothing is
  * launched).  Returns CCE_OK, CCE_EINVAL (misaligned, or pointer / size inconsistent) or CCE_EHIP.
  */

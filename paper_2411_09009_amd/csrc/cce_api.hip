@@ -628,6 +628,8 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
   if (sort && !mfma) return CCE_EUNSUPPORTED;   // vocabulary sorting exists on the bf16 MFMA path only
   const bool acc_bf16 = (opts->flags & (CCE_ACCUM_BF16 | CCE_ACCUM_KAHAN)) != 0;
   if (acc_bf16 && !mfma) return CCE_EUNSUPPORTED;   // so do the bf16 accumulation variants
+  // the MFMA gradient products address E with 32-bit byte offsets (whatever the workspace)
+  if (mfma && (uint64_t)N * (uint64_t)D * 2 >= ((uint64_t)1 << 32)) return CCE_EUNSUPPORTED;
   if (!opts->workspace) return CCE_EWORKSPACE;
   // the workspace is laid out for work lists whenever the flag asks for them (as sized by
   // cce_workspace_bytes); they are used only when nothing but filtered products reads GZ
@@ -651,9 +653,8 @@ int cce_backward_ex(const void* E, const void* C, const int64_t* targets, int64_
 
   if (mfma) {
     // ---- everything that can refuse the call, before the first launch
-    // the gradient products address E and a slab of C with 32-bit byte offsets
-    if ((uint64_t)N * (uint64_t)D * 2 >= ((uint64_t)1 << 32) || (uint64_t)vs * (uint64_t)D * 2 >= ((uint64_t)1 << 32))
-      return CCE_EUNSUPPORTED;
+    // ... and a slab of C likewise
+    if ((uint64_t)vs * (uint64_t)D * 2 >= ((uint64_t)1 << 32)) return CCE_EUNSUPPORTED;
     // a work-list entry packs the token tile and the slab-local vocabulary tile into 16 bits each,
     // and the tile-flag kernel puts the token tiles into grid.y
     if (lists_layout && (plan.Np / 256 > 65535 || vs / 256 > 65535)) return CCE_EUNSUPPORTED;

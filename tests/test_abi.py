@@ -22,7 +22,7 @@ def declared_symbols():
     return sorted(names)
 
 
-# The boundary: the two spec calls, their extended forms, the sizing / option / reporting helpers
+# The boundary: the two plain calls (cce_forward, cce_backward), their extended forms, the sizing / option / reporting helpers
 # they need, the registration that lends the plain calls their scratch, and the allocation-free forward.
 BOUNDARY = {"cce_forward", "cce_backward", "cce_forward_ex", "cce_backward_ex", "cce_workspace_bytes",
             "cce_block_max_bytes", "cce_strerror", "cce_default_opts", "cce_filter_block",

@@ -1,5 +1,5 @@
 """GPU parity: the HIP path, called through the C ABI, against the fp64 oracle on the
-same seeded inputs.  Tolerances (stated by the benchmark spec, restated here):
+same seeded inputs.  Tolerances:
   loss, LSE : max relative error <= 1e-3   (relative to max(|ref|, 1))
   dE, dC    : relative Frobenius error <= 1e-2 for bf16 storage with fp32 accumulation
 For fp32 storage the bounds used are 1e-5 / 1e-4 (fp32 FMA accumulation of D- and
@@ -416,7 +416,7 @@ def test_results_are_bitwise_reproducible(cce):
 
 
 def test_plain_entry_points_draw_on_the_lent_workspace(cce):
-    """cce_forward / cce_backward (the spec signatures) allocate nothing: their scratch is the
+    """cce_forward / cce_backward (the plain signatures, without options) allocate nothing: their scratch is the
     buffer registered with cce_set_workspace, and without one they refuse."""
     w = make("gemma2_2b", N=300, D=128, V=1000)
     E, C, t = to_device(w)
@@ -515,3 +515,57 @@ def test_calls_on_a_side_stream_and_under_graph_capture(cce):
         g.replay()
         torch.cuda.synchronize()
         assert torch.equal(loss, ref[0]) and torch.equal(dE, ref[1]) and torch.equal(dC, ref[2]), "replay %d" % k
+
+
+def test_more_tokens_than_a_filtered_dC_contraction_can_list(cce):
+    """N > 131072: the dC product's contraction over tokens is longer than the list of kept steps it keeps in LDS,
+    so it runs unfiltered whatever CCE_FILTER_DC says (documented); everything stays within the tolerances."""
+    w = make("stress_peaked", N=131072 + 256 + 5, D=64, V=700)
+    E, C, t = to_device(w)
+    loss, lse = run_forward(w, E, C, t)
+    ref_loss, ref_lse, rdE, rdC = oracle_all(w)
+    assert max_rel(f64(lse), ref_lse) <= TOL_LOSS and max_rel(f64(loss), ref_loss) <= TOL_LOSS
+    dloss = torch.from_numpy(w.mean_dloss()).cuda()
+    dE0, dC0, _ = run_backward(w, E, C, t, lse, dloss, eps=0.0)
+    assert rel_fro(f64(dE0), rdE) <= TOL_GRAD and rel_fro(f64(dC0), rdC) <= TOL_GRAD
+    assert max_row_err(f64(dE0), rdE) <= TOL_ROW and max_row_err(f64(dC0), rdC) <= TOL_ROW
+    dE1, dC1, st = run_backward(w, E, C, t, lse, dloss)                 # filters on: dC comes out as without
+    assert torch.equal(dC1, dC0) and 0 < st[1] <= st[0]
+    _, _, fdE, _ = oracle_all(w, eps=O.FILTER_EPS_BF16, mode="element")
+    assert rel_fro(f64(dE1), rdE) <= rel_fro(fdE, rdE) + rel_fro(f64(dE0), rdE) + 1e-3
+
+
+def test_largest_sizes_forward_works_and_backward_refuses_cleanly(cce):
+    """E of 4 GiB and more: the forward addresses it with 64-bit offsets; the MFMA backward, whose gradient
+    products use 32-bit byte offsets into E, refuses with CCE_EUNSUPPORTED before launching anything."""
+    N, D, V = (1 << 25) + 300, 64, 300                                  # N * D * 2 bytes = 4 GiB + 38 KB
+    g = torch.Generator(device="cuda")
+    g.manual_seed(5)
+    E = torch.randn(N, D, device="cuda", generator=g, dtype=torch.float32).to(torch.bfloat16)
+    C = (torch.randn(V, D, device="cuda", generator=g, dtype=torch.float32) * 0.3).to(torch.bfloat16)
+    t = torch.randint(0, V, (N,), device="cuda", generator=g)
+    o = L.make_opts(L.CCE_BF16)
+    ws = workspace(L.cce_workspace_bytes(L.CCE_OP_FORWARD, N, D, V, o))
+    o = L.make_opts(L.CCE_BF16, workspace=ws)
+    loss, lse = L.cce_forward_ex(E, C, t, 0.0, -100, o)
+    torch.cuda.synchronize()
+    # the oracle on sampled tokens, among them the first and the last ones and both sides of the 4 GiB line
+    rows = np.unique(np.concatenate([np.arange(0, 300), np.arange(N - 300, N), np.arange((1 << 25) - 150, (1 << 25) + 150),
+                                     np.random.default_rng(6).integers(0, N, 2000)]))
+    idx = torch.from_numpy(rows).cuda()
+    E_s = E[idx].float().cpu().numpy().astype(np.float64)
+    r_loss, r_lse = O.forward(E_s, C.float().cpu().numpy().astype(np.float64), t[idx].cpu().numpy(), 0.0, -100)
+    assert max_rel(f64(lse[idx]), r_lse) <= TOL_LOSS and max_rel(f64(loss[idx]), r_loss) <= TOL_LOSS
+    assert bool(torch.isfinite(lse).all())
+    wb = workspace(1 << 20)
+    ob = L.make_opts(L.CCE_BF16, workspace=wb)
+    dE = torch.full((4096,), 7.0, device="cuda")                        # stand-ins: nothing may be written
+    import ctypes
+    with pytest.raises(L.CceError) as ei:        # (straight through ctypes: the binding's wrapper would check the outputs' shapes)
+        st = L.load().cce_backward_ex(E.data_ptr(), C.data_ptr(), t.data_ptr(), N, D, V, 0.0, -100, lse.data_ptr(),
+                                      loss.data_ptr(), dE.data_ptr(), dE.data_ptr(), ctypes.byref(ob))
+        if st != 0:
+            raise L.CceError(st, L.cce_strerror(st))
+    assert ei.value.status == -3
+    torch.cuda.synchronize()
+    assert bool((dE == 7.0).all())
