@@ -181,7 +181,8 @@ int cce_forward_ex(const void* E, const void* C, const int64_t* targets,
  * before anything is launched: at the 8 vocabulary splits of a large batch that is N >= 131072
  * tokens, and any call with CCE_COMPACT_IGNORED whose copy of E does not fit.
  * Every call on one GPU shares that GPU's array, which keeps the previous call's contents
- * (never read: each call writes all the partials it merges).  Calls that overlap on one GPU
+ * (never read: each call writes all the partials it merges, and its forward kernel clears the
+ * one counter that must start at zero).  Calls that overlap on one GPU
  * (different streams, different threads) race on it; calls on one stream are safe.
  */
 int cce_forward_noalloc(const void* E, const void* C, const int64_t* targets,
