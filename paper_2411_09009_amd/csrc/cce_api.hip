@@ -749,8 +749,9 @@ int cce_forward_noalloc(const void* E, const void* C, const int64_t* targets, in
   st = static_scratch(&o.workspace);
   if (st != CCE_OK) return st;
   o.workspace_bytes = kStaticScratchBytes;
-  // The forward kernels write every (split, token) partial the finalize kernel reads, so nothing of
-  // the array has to start at zero: what an earlier call left in it is never read.
+  // The forward kernels write every (split, token) partial the finalize kernel reads, and the first of them
+  // clears the out-of-range-target counter at the head of the scratch: what an earlier call left in the
+  // array is never read.
   return cce_forward_ex(E, C, targets, N, D, V, softcap, ignore_index, out_loss, out_lse, &o);
 }
 
