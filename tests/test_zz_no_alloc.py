@@ -55,3 +55,28 @@ def test_problem_beyond_the_static_scratch_is_refused(cce):
     L.cce_forward_noalloc(E, C, t, 0.0, w.ignore_index, L.make_opts(L.CCE_BF16), loss, lse)
     torch.cuda.synchronize()
     assert torch.equal(loss, ref_loss) and torch.equal(lse, ref_lse)
+
+
+def test_forward_on_static_scratch_under_graph_capture(cce):
+    """The call allocates nothing and records no memset, so it can be captured into a HIP graph; every replay
+    (new inputs, eager work and a synchronisation in between) is checked against the eager result."""
+    w = make("gemma2_2b", N=900, D=128, V=4000)
+    E, C, t = to_device(w)
+    loss = torch.empty(w.N, device="cuda")
+    lse = torch.empty(w.N, device="cuda")
+    cap = torch.cuda.Stream()
+    cap.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=cap):
+        o = L.make_opts(L.CCE_BF16, stream=cap.cuda_stream)
+        L.cce_forward_noalloc(E, C, t, w.softcap, w.ignore_index, o, loss, lse)
+    E0 = E.clone()
+    for k in range(3):
+        E.copy_(E0.roll(k + 1, 0))
+        ref_loss, ref_lse = run_forward(w, E, C, t)          # eager, through cce_forward_ex
+        loss.zero_()
+        lse.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(loss, ref_loss) and torch.equal(lse, ref_lse), "replay %d" % k
