@@ -322,18 +322,7 @@ def configs_table():
     dev = torch.device("cuda:0")
 
     def timed(fn, iters=5):
-        for _ in range(3):
-            fn()
-        torch.cuda.synchronize()
-        ts = []
-        for _ in range(iters):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            fn()
-            e1.record()
-            torch.cuda.synchronize()
-            ts.append(e0.elapsed_time(e1))
-        return sum(ts) / len(ts)
+        return float(np.mean(_timed_ms(fn, iters, warm=3)))
 
     print("| config | N | D | V | cap | path | fwd ms | fwd % of 2.5 PF | bwd dense ms | bwd dense % | fwd+bwd dense k tok/s "
           "| bwd filtered ms | blocks kept | filtered + skip-tiles bwd ms | dE / dC filtered vs dense (rel. Frobenius) "
