@@ -111,7 +111,9 @@ def probe_table():
     for label, reads, dma in (("alone", 0, 0), ("+ 4 ds_read_b128 per 8 MFMAs (a 128 x 128 wave tile's rate)", 4, 0),
                               ("+ 6 ds_read_b128 per 8 MFMAs (the 128 x 64 wave tile's rate)", 6, 0),
                               ("+ 6 reads + direct-to-LDS loads of a 256 x 256 x 64 stage (L2 hits)", 6, 1),
-                              ("+ 4 reads + the same loads", 4, 1)):
+                              ("+ 4 reads + the same loads", 4, 1),
+                              ("+ 12 ds_read_b64_tr_b16 per 8 MFMAs (both operands K-major, as in the dC product)", 12, 0),
+                              ("+ 12 transposing reads + the same loads", 12, 1)):
         res = []
         for data in (real, torch.zeros_like(real)):
             ts = _timed_ms(lambda: probes.engine(data, out, blocks, iters, reads, dma), 3, 1)

@@ -28,6 +28,7 @@ int cce_probe_copy(void* dst, const void* src, size_t bytes, void* stream);
 
 /* The MFMA loop with the tile engine's other activities added one at a time (lds_reads = 0, 4 or 6
  * ds_read_b128 per 8 MFMAs: none, the rate of a 128 x 128 wave tile, the rate of the library's 128 x 64 one;
+ * 12: the same bytes as twelve ds_read_b64_tr_b16, as when both operands are K-major;
  * dma = 1: direct-to-LDS loads from an L2-resident buffer at the rate of a 256 x 256 x 64 stage).  `data`:
  * at least 8 MiB + 64 KiB of bf16 operand data; `out`: blocks * 512 floats; iters even.
  * flop = blocks * 8 * iters * 8 * 32768. */

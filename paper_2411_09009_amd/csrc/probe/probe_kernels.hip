@@ -32,7 +32,8 @@ __global__ __launch_bounds__(512) void mfma_probe_kernel(const bf16x8* __restric
 
 // The same loop with the tile engine's other activities added one at a time, to see what each costs when
 // the chip is limited by power rather than by issue slots: LDS fragment reads at the rate of a 128 x 64 wave
-// tile (6 ds_read_b128 per 8 MFMAs) or of a 128 x 128 one (4 per 8), and direct-to-LDS loads from a buffer
+// tile (6 ds_read_b128 per 8 MFMAs, or 12 transposing 8-byte reads when both operands are K-major) or of a
+// 128 x 128 one (4 per 8), and direct-to-LDS loads from a buffer
 // that stays in the L2 at the rate of a 256 x 256 x 64 stage (8 KB per wave per 32 MFMAs).
 #define CCE_PROBE_LDS(p) ((__attribute__((address_space(3))) void*)(p))
 #define CCE_PROBE_GLB(p) ((const __attribute__((address_space(1))) void*)(p))
@@ -57,7 +58,23 @@ __global__ __launch_bounds__(512) void engine_probe_kernel(const uint4* __restri
   // reads of iteration `it` fill nxt (highest byte touched: 53248 < 65536); cur feeds the MFMAs
   auto step = [&](int it, bf16x8 (&cur)[6], bf16x8 (&nxt)[6]) {
     const uint32_t a = base + (uint32_t)((it & 7) * 4096);
-    if (READS >= 4) {
+    if (READS == 12) {
+      // both operands K-major: two 8-byte transposing reads per fragment (highest byte touched: 55296 < 65536)
+      typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
+      typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+      u32x2_t t[12];
+#define CCE_PROBE_TR(i, off) asm volatile("ds_read_b64_tr_b16 %0, %1 offset:" #off : "=v"(t[i]) : "v"(a));
+      CCE_PROBE_TR(0, 0) CCE_PROBE_TR(1, 2048) CCE_PROBE_TR(2, 4096) CCE_PROBE_TR(3, 6144) CCE_PROBE_TR(4, 8192)
+      CCE_PROBE_TR(5, 10240) CCE_PROBE_TR(6, 12288) CCE_PROBE_TR(7, 14336) CCE_PROBE_TR(8, 16384)
+      CCE_PROBE_TR(9, 18432) CCE_PROBE_TR(10, 20480) CCE_PROBE_TR(11, 22528)
+#undef CCE_PROBE_TR
+      asm volatile("s_waitcnt lgkmcnt(0)"
+                   : "+v"(t[0]), "+v"(t[1]), "+v"(t[2]), "+v"(t[3]), "+v"(t[4]), "+v"(t[5]), "+v"(t[6]), "+v"(t[7]),
+                     "+v"(t[8]), "+v"(t[9]), "+v"(t[10]), "+v"(t[11]));
+#pragma unroll
+      for (int j = 0; j < 6; ++j)
+        nxt[j] = __builtin_bit_cast(bf16x8, (u32x4_t)__builtin_shufflevector(t[2 * j], t[2 * j + 1], 0, 1, 2, 3));
+    } else if (READS >= 4) {
       asm volatile("ds_read_b128 %0, %1" : "=v"(nxt[0]) : "v"(a));
       asm volatile("ds_read_b128 %0, %1 offset:4096" : "=v"(nxt[1]) : "v"(a));
       asm volatile("ds_read_b128 %0, %1 offset:8192" : "=v"(nxt[4]) : "v"(a));
@@ -77,7 +94,7 @@ __global__ __launch_bounds__(512) void engine_probe_kernel(const uint4* __restri
 #pragma unroll
     for (int j = 0; j < 8; ++j)
       acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur[j >> 1], cur[4 + (j & 1)], acc[j], 0, 0, 0);
-    if (READS)
+    if (READS && READS != 12)
       asm volatile("s_waitcnt lgkmcnt(0)"
                    : "+v"(nxt[0]), "+v"(nxt[1]), "+v"(nxt[2]), "+v"(nxt[3]), "+v"(nxt[4]), "+v"(nxt[5]));
   };
@@ -128,7 +145,8 @@ extern "C" int cce_probe_mfma(const void* frags, float* out, int blocks, int ite
 
 // Launches the engine-activity probe: `data` is a device buffer of at least 8 MiB + 64 KiB of bf16 operand
 // data (its first 64 KiB become the LDS contents, the rest is the source of the direct loads), `out` holds
-// blocks * 512 floats, `iters` is even.  lds_reads: 0, 4 or 6 ds_read_b128 per 8 MFMAs; dma: 0 / 1.
+// blocks * 512 floats, `iters` is even.  lds_reads: 0, 4 or 6 ds_read_b128 per 8 MFMAs, or 12
+// ds_read_b64_tr_b16 (both operands K-major); dma: 0 / 1.
 // flop = blocks * 8 waves * iters * 8 * 32768.  Returns a hipError_t value.
 extern "C" int cce_probe_engine(const void* data, float* out, int blocks, int iters, int lds_reads, int dma, void* stream) {
   if (!data || !out || blocks <= 0 || iters <= 0 || (iters & 1)) return (int)hipErrorInvalidValue;
@@ -143,6 +161,8 @@ extern "C" int cce_probe_engine(const void* data, float* out, int blocks, int it
   else if (lds_reads == 0 && dma) CCE_PROBE_LAUNCH(0, 1);
   else if (lds_reads == 4 && dma) CCE_PROBE_LAUNCH(4, 1);
   else if (lds_reads == 6 && dma) CCE_PROBE_LAUNCH(6, 1);
+  else if (lds_reads == 12 && !dma) CCE_PROBE_LAUNCH(12, 0);
+  else if (lds_reads == 12 && dma) CCE_PROBE_LAUNCH(12, 1);
   else return (int)hipErrorInvalidValue;
 #undef CCE_PROBE_LAUNCH
   return (int)hipGetLastError();
