@@ -11,6 +11,13 @@ For each configuration it stores, in tests/golden/<config>.npz:
   dC_rows, dC      int64 [r], float32 [r, D]   oracle dC for sampled vocabulary entries
   dE_f, dC_f       the same rows with the element-wise gradient filter at eps = 2^-12
                    (the finest granularity a block filter can be compared with)
+  tok_rows, voc_rows, cols        the >= 1024 tokens / >= 1024 vocabulary entries / 16 columns of sampling.py
+  dE_sub  float32 [tokens, 16]    oracle dE at (tok_rows, cols): sampled entries of >= 1024 rows, every token tile
+  dC_sub  float32 [entries, 16]   oracle dC at (voc_rows, cols): every slab of every slab width holds several
+  dE_norm, dC_norm  float64       Euclidean norm of each of those complete rows
+                   (a complete row would be 9 - 20 KB; 2048 of them per configuration do not belong in a repository:
+                   tests/test_full_size_gpu.py recomputes the complete rows with the oracle and checks them against
+                   these entries and norms before it compares the kernels with them)
   (upstream gradient = 1 / N_valid for every valid token)
   e_sum, c_sum, t_sum            checksums of the generated inputs, so that a test can
                                  verify it regenerated bit-identical inputs.
@@ -30,6 +37,8 @@ sys.path.insert(0, ROOT)
 
 from oracle import cce_oracle as O   # noqa: E402
 from workloads import CONFIGS, make  # noqa: E402
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+from sampling import sample_columns, sample_tokens, sample_vocab  # noqa: E402
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 FULL = ["small_vocab", "gemma2_2b", "llama3_8b", "stress", "stress_peaked", "gemma2_9b", "qwen25_7b", "gemma2_2b_n1024"]
@@ -86,10 +95,19 @@ def build(name, reuse_forward=False):
                               w.softcap, w.ignore_index, eps=eps)
     dC_f = O.backward_dC_rows(E64, C64, w.targets, lse, lam, vrows, w.softcap, w.ignore_index, eps=eps)
     print("%s: sampled backward oracle %.1f s" % (name, time.time() - t0), flush=True)
+    t0 = time.time()
+    tok, voc, cols = sample_tokens(w), sample_vocab(w), sample_columns(w)
+    wide_dE = O.backward_dE_rows(w.E64(tok), C64, w.targets[tok], lse[tok], lam[tok], np.arange(len(tok)),
+                                 w.softcap, w.ignore_index)
+    wide_dC = O.backward_dC_rows(E64, C64, w.targets, lse, lam, voc, w.softcap, w.ignore_index)
+    print("%s: %d + %d sampled rows %.1f s" % (name, len(tok), len(voc), time.time() - t0), flush=True)
     es, cs, ts = checksums(w)
     np.savez_compressed(path, lse=lse.astype(np.float32), loss=loss.astype(np.float32),
                         dE_rows=rows, dE=dE.astype(np.float32), dC_rows=vrows, dC=dC.astype(np.float32),
-                        dE_f=dE_f.astype(np.float32), dC_f=dC_f.astype(np.float32), e_sum=es, c_sum=cs, t_sum=ts, N=w.N, D=w.D, V=w.V)
+                        dE_f=dE_f.astype(np.float32), dC_f=dC_f.astype(np.float32), e_sum=es, c_sum=cs, t_sum=ts, N=w.N, D=w.D, V=w.V,
+                        tok_rows=tok, voc_rows=voc, cols=cols,
+                        dE_sub=wide_dE[:, cols].astype(np.float32), dC_sub=wide_dC[:, cols].astype(np.float32),
+                        dE_norm=np.linalg.norm(wide_dE, axis=1), dC_norm=np.linalg.norm(wide_dC, axis=1))
 
 
 def forward_chunked(w, C64):

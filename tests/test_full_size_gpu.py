@@ -3,14 +3,16 @@
 
 What the fp64 oracle supplies at these sizes:
   * stored (tests/golden/<config>.npz, written by tests/golden/make_golden.py, which calls only
-    oracle/ and the seeded generator): LSE and loss of EVERY token, plus 16 complete rows of dE and
-    dC with and without the element-wise filter;
+    oracle/ and the seeded generator): LSE and loss of EVERY token; 16 complete rows of dE and dC with
+    and without the element-wise filter; and, for >= 1024 sampled tokens and >= 1024 sampled vocabulary
+    entries, 16 entries of each row of dE / dC together with the norm of the complete row;
   * computed here, on the host, by the oracle itself from those stored LSEs: complete rows of dE
     for >= 1024 sampled tokens and complete rows of dC for >= 1024 sampled vocabulary entries.  A
     row of dE needs only its own token and all of C; a row of dC needs only its own logit column
     once the LSE of every token is known: both are exact restrictions of the full gradient, a few
-    seconds of fp64 each.  (Stored, they would be 20 - 80 MB per configuration.)
-    The samples hold both sides of every 256-token tile edge (dE) and of every multiple of 2048 in
+    seconds of fp64 each (stored in full they would be 20 - 80 MB per configuration), and checked here
+    against the stored entries and norms before the kernels are compared with them.
+    The samples (tests/golden/sampling.py) hold both sides of every 256-token tile edge (dE) and of every multiple of 2048 in
     the vocabulary (dC): every slab edge of the recommended (6144 k) and of the wide (16384 k,
     24576 k) slab width, so that each slab of either width has at least its first and its last row
     checked; the ragged last tile's edges; the most frequent and never-used targets; ignored tokens;
@@ -41,6 +43,7 @@ from oracle import cce_oracle as O
 from workloads import make
 
 from gpu_util import f64, max_rel, max_row_err, rel_fro, run_backward, run_forward, to_device
+from golden.sampling import sample_columns, sample_tokens, sample_vocab
 
 pytestmark = pytest.mark.gpu
 
@@ -53,44 +56,10 @@ TOL_GRAD = 1e-2
 TOL_ROW = 1e-2
 # distance of the default-filtered dE rows from the EXACT gradient (see the module docstring)
 FILTERED_DE_BOUND = {"gemma2_2b": 2.5e-2, "gemma2_9b": 2.5e-2, "gemma2_2b_n1024": 2.5e-2}
-ROWS = 1024
 
 
 def rows_of(t, rows):
     return f64(t[torch.from_numpy(np.asarray(rows)).to(t.device)])
-
-
-def sample_tokens(w, count=ROWS):
-    rng = np.random.default_rng(2000 + w.spec.seed)
-    rows = {0, w.N - 1}
-    for e in range(256, w.N, 256):                     # both sides of every token-tile edge
-        rows |= {e - 1, e}
-    ign = np.nonzero(w.targets == w.ignore_index)[0]
-    rows |= {int(i) for i in ign[:8]}
-    rows = {r for r in rows if 0 <= r < w.N}
-    while len(rows) < min(count, w.N):
-        rows.add(int(rng.integers(0, w.N)))
-    return np.array(sorted(rows))
-
-
-def sample_vocab(w, count=ROWS):
-    rng = np.random.default_rng(3000 + w.spec.seed)
-    rows = {0, w.V - 1}
-    for e in range(2048, w.V, 2048):                   # every slab edge of every slab width in use
-        rows |= {e - 1, e}
-    last_tile = (w.V - 1) // 256 * 256                 # the (possibly ragged) last vocabulary tile
-    rows |= {last_tile - 1, last_tile, w.V - 2}
-    valid_t = w.targets[w.targets != w.ignore_index]
-    counts = np.bincount(valid_t, minlength=w.V)
-    rows |= {int(v) for v in np.argsort(-counts)[:8]}
-    never = np.nonzero(counts == 0)[0]
-    rows |= {int(v) for v in never[:: max(len(never) // 8, 1)][:8]}
-    if w.boosted is not None:
-        rows |= {int(v) for v in w.boosted[:: max(len(w.boosted) // 16, 1)]}
-    rows = {r for r in rows if 0 <= r < w.V}
-    while len(rows) < min(count, w.V):
-        rows.add(int(rng.integers(0, w.V)))
-    return np.array(sorted(rows))
 
 
 def load_golden(name, w):
@@ -106,21 +75,37 @@ def load_golden(name, w):
 
 
 def check_sampled_rows(name, w, g, dE, dC, what):
-    """>= 1024 rows of dE and of dC against the oracle's (computed now, from the stored LSEs)."""
+    """>= 1024 rows of dE and of dC: first the kernels against the stored oracle entries (16 columns of every
+    sampled row), then against complete rows the oracle computes now from the stored LSEs, which are themselves
+    checked against the stored entries and row norms."""
     t0 = time.time()
+    tok, voc, cols = sample_tokens(w), sample_vocab(w), sample_columns(w)
+    assert np.array_equal(tok, g["tok_rows"]) and np.array_equal(voc, g["voc_rows"]) and np.array_equal(cols, g["cols"])
+    got_dE, got_dC = rows_of(dE, tok), rows_of(dC, voc)
+    sE, sC = g["dE_sub"].astype(np.float64), g["dC_sub"].astype(np.float64)
+    eE_s, eC_s = rel_fro(got_dE[:, cols], sE), rel_fro(got_dC[:, cols], sC)
+    assert eE_s <= TOL_GRAD and eC_s <= TOL_GRAD
+    # every sampled row on its own, scaled by the stored norm of the complete row (16 of D entries are seen)
+    scale = np.sqrt(len(cols) / w.D)
+    for got, sub, norm in ((got_dE, sE, g["dE_norm"]), (got_dC, sC, g["dC_norm"])):
+        floor = float(np.median(norm)) or 1.0
+        worst = np.max(np.linalg.norm(got[:, cols] - sub, axis=1) / (np.maximum(norm, floor) * scale))
+        assert worst <= 3 * TOL_ROW, worst                  # 16 entries stand for a row: looser than the complete rows below
     lse = g["lse"].astype(np.float64)
     lam = w.mean_dloss().astype(np.float64)
     C64 = w.C64()
-    tok, voc = sample_tokens(w), sample_vocab(w)
     ref_dE = O.backward_dE_rows(w.E64(tok), C64, w.targets[tok], lse[tok], lam[tok], np.arange(len(tok)),
                                 w.softcap, w.ignore_index)
     ref_dC = O.backward_dC_rows(w.E64(), C64, w.targets, lse, lam, voc, w.softcap, w.ignore_index)
     del C64
-    got_dE, got_dC = rows_of(dE, tok), rows_of(dC, voc)
+    # the rows computed here are the ones the committed script stored entries and norms of
+    assert np.allclose(ref_dE[:, cols], sE, rtol=1e-5, atol=1e-12) and np.allclose(ref_dC[:, cols], sC, rtol=1e-5, atol=1e-12)
+    assert np.allclose(np.linalg.norm(ref_dE, axis=1), g["dE_norm"], rtol=1e-9, atol=1e-15)
+    assert np.allclose(np.linalg.norm(ref_dC, axis=1), g["dC_norm"], rtol=1e-9, atol=1e-15)
     eE, eC = rel_fro(got_dE, ref_dE), rel_fro(got_dC, ref_dC)
     rE, rC = max_row_err(got_dE, ref_dE), max_row_err(got_dC, ref_dC)
-    print("  %s: %d dE rows err %.2e (worst row %.2e)  %d dC rows err %.2e (worst row %.2e)  [oracle %.0f s]"
-          % (what, len(tok), eE, rE, len(voc), eC, rC, time.time() - t0), flush=True)
+    print("  %s: %d dE rows err %.2e (worst row %.2e; stored entries %.2e)  %d dC rows err %.2e (worst row %.2e; stored entries %.2e)"
+          "  [oracle %.0f s]" % (what, len(tok), eE, rE, eE_s, len(voc), eC, rC, eC_s, time.time() - t0), flush=True)
     assert eE <= TOL_GRAD and eC <= TOL_GRAD
     assert rE <= TOL_ROW and rC <= TOL_ROW
     return tok, voc, ref_dE, ref_dC
